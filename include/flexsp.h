@@ -1,0 +1,214 @@
+/*
+ * flexsp.h - C ABI of the MI355X (gfx950) library for one device's share of
+ * Ulysses-style sequence parallelism with heterogeneous groups (FlexSP).
+ *
+ * After the sequence-to-head exchange (paper Sec. 2.1.2, Eq. 2) a device holds H/P
+ * attention heads for a packed stream of complete, variable-length sequences
+ * (Sec. 2.2.2, sequence packing) and evaluates attention on them (Eq. 3); the result goes
+ * back through the inverse exchange (Eq. 4).  This library provides, for one GPU:
+ *
+ *   flexsp_pack / flexsp_unpack   the local layout permute either side of the exchange,
+ *   flexsp_plan_create            the per-micro-batch tile plan (lengths are known on the
+ *                                 host before the step, Sec. 5 "Disaggregating Solving
+ *                                 and Training"),
+ *   flexsp_attn_varlen_fwd / _bwd Eq. 3 and its gradient over the packed stream.
+ *
+ * Conventions
+ *   - Every function returns FLEXSP_OK (0) or a negative flexsp_status; nothing throws or
+ *     aborts.  Arguments are validated before anything is launched.
+ *   - "device pointer" = memory of the GPU the context was created on, owned by the
+ *     caller; "host pointer" = ordinary host memory, copied before the call returns.
+ *   - The four hot calls (pack, unpack, fwd, bwd) are asynchronous on the caller's HIP
+ *     stream, allocate nothing and never synchronise the host.
+ *   - The library owns only contexts and plans.  A plan may be used by one in-flight
+ *     forward and one in-flight backward at a time (each has its own queue counters);
+ *     launches that share a plan must be ordered on one stream or by events.
+ *   - There is no CPU fallback: without a usable gfx950 device the hot calls fail.
+ */
+#ifndef FLEXSP_H
+#define FLEXSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum flexsp_status {
+    FLEXSP_OK = 0,
+    FLEXSP_INVALID_ARGUMENT = -1, /* null pointer, negative size, non-monotone cu_seqlens, ... */
+    FLEXSP_UNSUPPORTED = -2,      /* head dim not in {64,128}, element size not in {1,2,4,8,16}, ... */
+    FLEXSP_PLAN_MISMATCH = -3,    /* call arguments disagree with the plan they were given */
+    FLEXSP_HIP_ERROR = -4,        /* a HIP runtime call failed (see flexsp_last_hip_error) */
+    FLEXSP_OUT_OF_MEMORY = -5,
+    FLEXSP_NO_DEVICE = -6         /* no gfx950 device / context is host-only */
+} flexsp_status;
+
+/* Element type of the gradients written by the backward call. */
+typedef enum flexsp_dtype { FLEXSP_BF16 = 0, FLEXSP_F32 = 1 } flexsp_dtype;
+
+typedef struct flexsp_ctx flexsp_ctx;   /* opaque: device id, CU / XCD counts            */
+typedef struct flexsp_plan flexsp_plan; /* opaque: tile queues (device + host copy), delta */
+typedef void *flexsp_stream;            /* a hipStream_t owned by the caller; NULL = default stream */
+
+/* Static, human-readable text for a status code. */
+const char *flexsp_strerror(int status);
+/* The hipError_t (as int) of the most recent FLEXSP_HIP_ERROR on this thread. */
+int flexsp_last_hip_error(void);
+/* Library version, "major.minor". */
+const char *flexsp_version(void);
+
+/*
+ * Context.  flexsp_ctx_create binds to HIP device `device` (>= 0) and fails with
+ * FLEXSP_NO_DEVICE if it does not exist or is not gfx950.  device == -1 creates a
+ * HOST-ONLY context: plans can be built and inspected with it (for tests of the host
+ * logic), every launch through it fails with FLEXSP_NO_DEVICE.
+ */
+int flexsp_ctx_create(flexsp_ctx **out, int device);
+void flexsp_ctx_destroy(flexsp_ctx *ctx);
+/* Number of compute units / XCDs the scheduler assumes (0 / 8 for a host-only context). */
+int flexsp_ctx_num_cu(const flexsp_ctx *ctx);
+int flexsp_ctx_num_xcd(const flexsp_ctx *ctx);
+
+/*
+ * Tile plan for one packed batch.
+ *   cu_seqlens_host  host pointer, B+1 int32 prefix sums: cu[0] = 0, non-decreasing,
+ *                    cu[B] = T (tokens).  Sequence b owns tokens cu[b] .. cu[b+1]-1.
+ *                    Empty sequences are allowed and contribute nothing.
+ *   Hq, Hkv          query / key-value heads THIS GPU holds; Hq % Hkv == 0 (query head h
+ *                    reads kv head h / (Hq/Hkv)).
+ *   D                head dim, 64 or 128.
+ *   causal           nonzero: key j of a sequence is visible to query i iff j <= i.
+ * The plan lists work items (sequence, tile, head), longest first, in one queue per XCD,
+ * for the forward kernel and for the two backward kernels, and holds the fp32 scratch
+ * (delta [Hq, T]) the backward needs, so the hot calls allocate nothing.
+ * Everything is copied; the caller keeps ownership of cu_seqlens_host.
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED (D), OUT_OF_MEMORY, HIP_ERROR.
+ */
+int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu_seqlens_host, int32_t B,
+                       int32_t Hq, int32_t Hkv, int32_t D, int causal, flexsp_plan **out);
+void flexsp_plan_destroy(flexsp_plan *plan);
+
+/* Plan inspection (host logic; works for host-only contexts). */
+typedef struct flexsp_item {
+    int32_t seq_start; /* first token of the sequence in the packed stream            */
+    int32_t seq_len;   /* its length                                                   */
+    int32_t tile;      /* tile index inside the sequence (query tile or key tile)      */
+    int32_t head;      /* query head (forward, dQ pass) or kv head (dK/dV pass)        */
+} flexsp_item;
+enum { FLEXSP_PASS_FWD = 0, FLEXSP_PASS_BWD_DKV = 1, FLEXSP_PASS_BWD_DQ = 2 };
+/* Number of items of a pass, or a negative status. */
+int64_t flexsp_plan_num_items(const flexsp_plan *plan, int pass);
+/* Copies the items of a pass in queue order (queue 0 first) into `items` (host pointer,
+ * capacity >= num_items) and the num_xcd+1 queue boundaries into `queue_offsets` (host
+ * pointer, may be NULL). */
+int flexsp_plan_get_items(const flexsp_plan *plan, int pass, flexsp_item *items,
+                          int64_t capacity, int64_t *queue_offsets);
+/* Rows per tile used by a pass (query rows for FWD and BWD_DQ, key rows for BWD_DKV). */
+int flexsp_plan_tile_rows(const flexsp_plan *plan, int pass);
+/* Bytes of device scratch the plan holds for the backward pass. */
+size_t flexsp_attn_bwd_workspace_bytes(const flexsp_plan *plan);
+
+/*
+ * Layout permute, the local half of the exchanges in Eq. 2 / Eq. 4 (Sec. 2.1.2): a device
+ * holds T tokens x all H heads ("sequence-sharded", Q_s in the paper) and regroups them
+ * into one contiguous slab per peer, each slab holding H/P heads ("head-sharded", Q_h):
+ *
+ *   pack:    dst[r, t, h, :] = src[t, r*(H/P) + h, :]      src [T, H, D] -> dst [P, T, H/P, D]
+ *   unpack:  dst[t, r*(H/P) + h, :] = src[r, t, h, :]      src [P, T, H/P, D] -> dst [T, H, D]
+ *
+ * Tokens are split evenly over the group irrespective of sequence boundaries (Sec. 4.1.2),
+ * so no cu_seqlens is involved.  src and dst are device pointers to dense row-major
+ * tensors of `elem_bytes`-byte elements (1, 2, 4, 8 or 16; pure bit copy), must not
+ * overlap, and need T*H*D*elem_bytes bytes each.  Requires H % P == 0.  T == 0 is a no-op.
+ * 16-byte accesses are used when (H/P)*D*elem_bytes and both base addresses are multiples
+ * of 16, narrower ones otherwise.
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED, NO_DEVICE, HIP_ERROR.
+ */
+int flexsp_pack(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_t H, int32_t D,
+                int32_t P, int32_t elem_bytes, flexsp_stream stream);
+int flexsp_unpack(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_t H, int32_t D,
+                  int32_t P, int32_t elem_bytes, flexsp_stream stream);
+
+/*
+ * Strided view of a [T, heads, D] bf16 tensor in device memory: element (t, h, d) lives at
+ * ptr + (t*stride_token + h*stride_head + d) elements.  The last dim is contiguous, ptr and
+ * both strides (in elements) must keep every row 16-byte aligned (multiples of 8 elements).
+ * A view lets a heads subset of a larger tensor be used in place.
+ */
+typedef struct flexsp_tensor {
+    void *ptr;
+    int64_t stride_token;
+    int64_t stride_head;
+} flexsp_tensor;
+
+/*
+ * Forward of Eq. 3 over the packed stream, per sequence and per head:
+ *   O[i,h,:] = sum_j softmax_j(scale * q[i,h,:].k[j,g,:]) v[j,g,:],  g = kv head of h,
+ *   j over the keys of i's own sequence (j <= i when causal),
+ *   LSE[h,i] = natural-log-sum-exp of the scaled scores of row i.
+ *   q, o              views of [T, *, D] bf16; heads head_begin .. head_begin+head_count-1 are used
+ *   k, v              views of [T, *, D] bf16; kv heads kv_head_begin .. +kv_head_count-1
+ *   cu_seqlens_dev    device pointer, B+1 int32, same values the plan was built from
+ *   head_count, kv_head_count must equal the plan's Hq, Hkv
+ *   softmax_scale     <= 0 selects 1/sqrt(D)
+ *   lse               device pointer, fp32 [head_count, T]
+ * Scores and softmax statistics are fp32; P is rounded to bf16 before the PV product;
+ * accumulation is fp32; O is rounded to bf16 once.
+ * Errors: INVALID_ARGUMENT, PLAN_MISMATCH, NO_DEVICE, HIP_ERROR.
+ */
+int flexsp_attn_varlen_fwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                           flexsp_tensor v, const int32_t *cu_seqlens_dev, int32_t head_begin,
+                           int32_t head_count, int32_t kv_head_begin, int32_t kv_head_count,
+                           int causal, float softmax_scale, flexsp_tensor o, float *lse,
+                           flexsp_stream stream);
+
+/*
+ * Backward of Eq. 3 for the loss L = sum(O * dO): writes dq [T,*,D] (query heads as in q)
+ * and dk, dv [T,*,D] (kv heads as in k; summed over the query heads of each group).
+ * o and lse are the forward's outputs.  Softmax is recomputed from lse (no second
+ * reduction); delta = rowsum(dO * O) is formed in fp32 in the plan's scratch.
+ * grad_dtype selects the element type of dq, dk and dv (their strides count elements of that
+ * type): FLEXSP_BF16 rounds the fp32 accumulators to bf16 once; FLEXSP_F32 stores them as
+ * they are (useful when grouped-query sums grow past the range where bf16's spacing is fine
+ * enough).  Results are deterministic (no floating-point atomics).
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED (grad_dtype), PLAN_MISMATCH, NO_DEVICE, HIP_ERROR.
+ */
+int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                           flexsp_tensor v, flexsp_tensor o, flexsp_tensor dO, const float *lse,
+                           const int32_t *cu_seqlens_dev, int32_t head_begin, int32_t head_count,
+                           int32_t kv_head_begin, int32_t kv_head_count, int causal,
+                           float softmax_scale, flexsp_tensor dq, flexsp_tensor dk,
+                           flexsp_tensor dv, int32_t grad_dtype, flexsp_stream stream);
+
+/*
+ * Per-kernel timing for benchmarks.  Between flexsp_profile_start and flexsp_profile_stop every
+ * kernel launched through `ctx` is bracketed by a pair of HIP events on the caller's stream.
+ * flexsp_profile_stop waits for the recorded events (it synchronises the host), adds up the
+ * elapsed time and the number of launches per kernel and turns recording off.  At most
+ * `max_launches` launches are recorded (events are created by flexsp_profile_start, none in
+ * the hot calls); later ones run untimed and are counted in `dropped`.
+ * Errors: INVALID_ARGUMENT, NO_DEVICE, HIP_ERROR, OUT_OF_MEMORY.
+ */
+enum {
+    FLEXSP_K_PACK = 0,
+    FLEXSP_K_UNPACK = 1,
+    FLEXSP_K_FWD = 2,
+    FLEXSP_K_BWD_DELTA = 3,
+    FLEXSP_K_BWD_DKV = 4,
+    FLEXSP_K_BWD_DQ = 5,
+    FLEXSP_K_COUNT = 6
+};
+typedef struct flexsp_profile {
+    double ms[FLEXSP_K_COUNT];        /* summed kernel time, milliseconds */
+    int64_t launches[FLEXSP_K_COUNT]; /* launches recorded                */
+    int64_t dropped;                  /* launches beyond max_launches     */
+} flexsp_profile;
+int flexsp_profile_start(flexsp_ctx *ctx, int32_t max_launches);
+int flexsp_profile_stop(flexsp_ctx *ctx, flexsp_profile *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXSP_H */

@@ -1,0 +1,246 @@
+"""ctypes binding of libflexsp.so: argument marshalling only.
+
+Function names are those of include/flexsp.h.  Tensors are torch tensors living on the
+GPU (torch is used for device memory and streams, nothing else); every step of the path
+runs inside the library's HIP kernels.  There is no fallback: if the shared library is
+missing the import of a symbol raises, and without a gfx950 device ``Context(0)`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from ctypes import POINTER, Structure, byref, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+from pathlib import Path
+
+import numpy as np
+
+LIB_PATH = Path(__file__).resolve().parent / "libflexsp.so"
+
+OK, INVALID_ARGUMENT, UNSUPPORTED, PLAN_MISMATCH, HIP_ERROR, OUT_OF_MEMORY, NO_DEVICE = 0, -1, -2, -3, -4, -5, -6
+PASS_FWD, PASS_BWD_DKV, PASS_BWD_DQ = 0, 1, 2
+BF16, F32 = 0, 1
+
+EXPORTS = (
+    "flexsp_strerror", "flexsp_last_hip_error", "flexsp_version",
+    "flexsp_ctx_create", "flexsp_ctx_destroy", "flexsp_ctx_num_cu", "flexsp_ctx_num_xcd",
+    "flexsp_plan_create", "flexsp_plan_destroy", "flexsp_plan_num_items", "flexsp_plan_get_items",
+    "flexsp_plan_tile_rows", "flexsp_attn_bwd_workspace_bytes",
+    "flexsp_pack", "flexsp_unpack", "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd",
+    "flexsp_profile_start", "flexsp_profile_stop",
+)
+KERNELS = ("pack", "unpack", "fwd", "bwd_delta", "bwd_dkv", "bwd_dq")
+
+
+class FlexspError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().flexsp_strerror(status).decode()
+        if status == HIP_ERROR:
+            msg += " (hipError %d)" % lib().flexsp_last_hip_error()
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+class Tensor(Structure):
+    _fields_ = [("ptr", c_void_p), ("stride_token", c_int64), ("stride_head", c_int64)]
+
+
+class Item(Structure):
+    _fields_ = [("seq_start", c_int32), ("seq_len", c_int32), ("tile", c_int32), ("head", c_int32)]
+
+
+class Profile(Structure):
+    _fields_ = [("ms", ctypes.c_double * 6), ("launches", c_int64 * 6), ("dropped", c_int64)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libflexsp.so (built in-tree by paper_2412_01523_amd.build); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{LIB_PATH} not built: run `python -m paper_2412_01523_amd.build` (needs hipcc)")
+        # torch ships its own HIP runtime (soname libamdhip64.so.7).  Load it first so that this
+        # library binds to the same runtime instance that owns torch's device memory and streams;
+        # two runtimes in one process do not see each other's allocations.
+        import torch  # noqa: F401
+        L = ctypes.CDLL(str(LIB_PATH))
+        L.flexsp_strerror.restype = c_char_p
+        L.flexsp_strerror.argtypes = [c_int]
+        L.flexsp_version.restype = c_char_p
+        L.flexsp_last_hip_error.restype = c_int
+        L.flexsp_ctx_create.argtypes = [POINTER(c_void_p), c_int]
+        L.flexsp_ctx_destroy.argtypes = [c_void_p]
+        L.flexsp_ctx_destroy.restype = None
+        L.flexsp_ctx_num_cu.argtypes = [c_void_p]
+        L.flexsp_ctx_num_xcd.argtypes = [c_void_p]
+        L.flexsp_plan_create.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int,
+                                         POINTER(c_void_p)]
+        L.flexsp_plan_destroy.argtypes = [c_void_p]
+        L.flexsp_plan_destroy.restype = None
+        L.flexsp_plan_num_items.argtypes = [c_void_p, c_int]
+        L.flexsp_plan_num_items.restype = c_int64
+        L.flexsp_plan_get_items.argtypes = [c_void_p, c_int, c_void_p, c_int64, c_void_p]
+        L.flexsp_plan_tile_rows.argtypes = [c_void_p, c_int]
+        L.flexsp_attn_bwd_workspace_bytes.argtypes = [c_void_p]
+        L.flexsp_attn_bwd_workspace_bytes.restype = c_size_t
+        perm = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32, c_int32, c_void_p]
+        L.flexsp_pack.argtypes = perm
+        L.flexsp_unpack.argtypes = perm
+        L.flexsp_attn_varlen_fwd.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, c_void_p, c_int32,
+                                             c_int32, c_int32, c_int32, c_int, c_float, Tensor, c_void_p,
+                                             c_void_p]
+        L.flexsp_attn_varlen_bwd.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, Tensor, Tensor,
+                                             c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int,
+                                             c_float, Tensor, Tensor, Tensor, c_int32, c_void_p]
+        L.flexsp_profile_start.argtypes = [c_void_p, c_int32]
+        L.flexsp_profile_stop.argtypes = [c_void_p, POINTER(Profile)]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise FlexspError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def _view(t) -> Tensor:
+    """[T, heads, D] torch tensor (2-byte elements, last dim contiguous) -> flexsp_tensor."""
+    assert t.dim() == 3 and t.stride(2) == 1 and t.element_size() in (2, 4), "need [T,H,D], D contiguous"
+    return Tensor(t.data_ptr(), t.stride(0), t.stride(1))
+
+
+class Context:
+    """flexsp_ctx.  device=-1 gives a host-only context (plan inspection without a GPU)."""
+
+    def __init__(self, device: int = 0):
+        self.handle = c_void_p()
+        _check(lib().flexsp_ctx_create(byref(self.handle), device), "flexsp_ctx_create")
+        self.device = device
+
+    @property
+    def num_cu(self) -> int:
+        return lib().flexsp_ctx_num_cu(self.handle)
+
+    @property
+    def num_xcd(self) -> int:
+        return lib().flexsp_ctx_num_xcd(self.handle)
+
+    def profile_start(self, max_launches: int = 4096):
+        _check(lib().flexsp_profile_start(self.handle, max_launches), "flexsp_profile_start")
+
+    def profile_stop(self) -> dict:
+        """{kernel: (total ms, launches)} for the launches since profile_start; synchronises."""
+        p = Profile()
+        _check(lib().flexsp_profile_stop(self.handle, byref(p)), "flexsp_profile_stop")
+        out = {name: (p.ms[i], int(p.launches[i])) for i, name in enumerate(KERNELS)}
+        out["dropped"] = int(p.dropped)
+        return out
+
+    def close(self):
+        if self.handle:
+            lib().flexsp_ctx_destroy(self.handle)
+            self.handle = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Plan:
+    """flexsp_plan built from HOST cu_seqlens (int32 prefix sums)."""
+
+    def __init__(self, ctx: Context, cu_seqlens_host, hq: int, hkv: int, d: int, causal: bool = True):
+        cu = np.ascontiguousarray(cu_seqlens_host, dtype=np.int32)
+        assert cu.ndim == 1 and len(cu) >= 1
+        self.ctx = ctx
+        self.handle = c_void_p()
+        self.cu = cu
+        self.hq, self.hkv, self.d, self.causal = hq, hkv, d, bool(causal)
+        _check(lib().flexsp_plan_create(ctx.handle, cu.ctypes.data_as(c_void_p), len(cu) - 1, hq, hkv, d,
+                                        int(bool(causal)), byref(self.handle)), "flexsp_plan_create")
+
+    def num_items(self, which: int) -> int:
+        n = lib().flexsp_plan_num_items(self.handle, which)
+        if n < 0:
+            raise FlexspError(int(n), "flexsp_plan_num_items")
+        return int(n)
+
+    def items(self, which: int):
+        """(items as a structured numpy array, queue offsets)"""
+        n = self.num_items(which)
+        arr = np.zeros(n, dtype=np.dtype([("seq_start", "<i4"), ("seq_len", "<i4"), ("tile", "<i4"),
+                                          ("head", "<i4")]))
+        offs = np.zeros(self.ctx.num_xcd + 1, dtype=np.int64)
+        _check(lib().flexsp_plan_get_items(self.handle, which, arr.ctypes.data_as(c_void_p), n,
+                                           offs.ctypes.data_as(c_void_p)), "flexsp_plan_get_items")
+        return arr, offs
+
+    def tile_rows(self, which: int) -> int:
+        return lib().flexsp_plan_tile_rows(self.handle, which)
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().flexsp_attn_bwd_workspace_bytes(self.handle))
+
+    def close(self):
+        if self.handle:
+            lib().flexsp_plan_destroy(self.handle)
+            self.handle = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def flexsp_pack(ctx: Context, src, dst, P: int, stream=None):
+    """src [T,H,D] -> dst [P,T,H/P,D] (dense torch tensors on the context's GPU)."""
+    T, H, D = src.shape
+    assert src.is_contiguous() and dst.is_contiguous() and dst.numel() == src.numel()
+    _check(lib().flexsp_pack(ctx.handle, src.data_ptr(), dst.data_ptr(), T, H, D, P, src.element_size(),
+                             _stream(stream)), "flexsp_pack")
+
+
+def flexsp_unpack(ctx: Context, src, dst, stream=None):
+    """src [P,T,Hp,D] -> dst [T,P*Hp,D]."""
+    P, T, Hp, D = src.shape
+    assert src.is_contiguous() and dst.is_contiguous() and dst.numel() == src.numel()
+    _check(lib().flexsp_unpack(ctx.handle, src.data_ptr(), dst.data_ptr(), T, P * Hp, D, P,
+                               src.element_size(), _stream(stream)), "flexsp_unpack")
+
+
+def flexsp_attn_varlen_fwd(ctx: Context, plan: Plan, q, k, v, cu_seqlens_dev, o, lse, *, head_begin=0,
+                           head_count=None, kv_head_begin=0, kv_head_count=None, causal=True,
+                           softmax_scale=0.0, stream=None):
+    head_count = plan.hq if head_count is None else head_count
+    kv_head_count = plan.hkv if kv_head_count is None else kv_head_count
+    _check(lib().flexsp_attn_varlen_fwd(ctx.handle, plan.handle, _view(q), _view(k), _view(v),
+                                        cu_seqlens_dev.data_ptr(), head_begin, head_count, kv_head_begin,
+                                        kv_head_count, int(bool(causal)), float(softmax_scale), _view(o),
+                                        lse.data_ptr(), _stream(stream)), "flexsp_attn_varlen_fwd")
+
+
+def flexsp_attn_varlen_bwd(ctx: Context, plan: Plan, q, k, v, o, dO, lse, cu_seqlens_dev, dq, dk, dv, *,
+                           head_begin=0, head_count=None, kv_head_begin=0, kv_head_count=None, causal=True,
+                           softmax_scale=0.0, stream=None):
+    head_count = plan.hq if head_count is None else head_count
+    kv_head_count = plan.hkv if kv_head_count is None else kv_head_count
+    assert dq.element_size() == dk.element_size() == dv.element_size()
+    grad_dtype = F32 if dq.element_size() == 4 else BF16      # gradient tensors are bf16 or fp32
+    _check(lib().flexsp_attn_varlen_bwd(ctx.handle, plan.handle, _view(q), _view(k), _view(v), _view(o),
+                                        _view(dO), lse.data_ptr(), cu_seqlens_dev.data_ptr(), head_begin,
+                                        head_count, kv_head_begin, kv_head_count, int(bool(causal)),
+                                        float(softmax_scale), _view(dq), _view(dk), _view(dv),
+                                        grad_dtype, _stream(stream)), "flexsp_attn_varlen_bwd")

@@ -1,0 +1,562 @@
+// Host side of libflexsp: contexts, tile plans, argument validation and the extern "C"
+// entry points declared in include/flexsp.h.  No kernel lives here.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "flexsp_internal.h"
+
+using namespace flexsp;
+
+struct EventPair {
+    hipEvent_t start, stop;
+    int kernel;
+};
+
+struct flexsp_ctx {
+    int device;  // -1: host-only
+    int num_cu;
+    int num_xcd;
+    // profiling: a pool of event pairs created by flexsp_profile_start
+    bool profiling;
+    std::vector<EventPair> events;
+    size_t events_used;
+    int64_t dropped;
+};
+
+struct HostPass {
+    std::vector<flexsp_item> items;     // queue order
+    int64_t offsets[kMaxQueues + 1];    // queue boundaries
+    int tile_rows;
+};
+
+struct flexsp_plan {
+    flexsp_ctx *ctx;
+    int32_t B, Hq, Hkv, D, causal;
+    int64_t T;
+    std::vector<int32_t> cu;
+    HostPass pass[3];
+    // device side (null for host-only plans): one allocation, carved up
+    void *dev_base;
+    size_t dev_bytes;
+    PassQueues dq[3];
+    float *delta;
+    size_t delta_bytes;
+};
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return e == hipErrorOutOfMemory ? FLEXSP_OUT_OF_MEMORY : FLEXSP_HIP_ERROR;
+}
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Brackets one kernel launch with a pair of events while profiling is on.
+struct Timed {
+    flexsp_ctx *ctx;
+    hipStream_t stream;
+    EventPair *ev;
+    Timed(flexsp_ctx *c, int kernel, hipStream_t s) : ctx(c), stream(s), ev(nullptr)
+    {
+        if (!c->profiling) return;
+        if (c->events_used >= c->events.size()) {
+            c->dropped++;
+            return;
+        }
+        ev = &c->events[c->events_used++];
+        ev->kernel = kernel;
+        (void)hipEventRecord(ev->start, stream);
+    }
+    ~Timed()
+    {
+        if (ev) (void)hipEventRecord(ev->stop, stream);
+    }
+};
+
+struct Work {
+    flexsp_item it;
+    int64_t cost;   // inner-loop steps of this item
+    int32_t group;  // (sequence, head) group id
+};
+
+// Builds one pass: lists the items, spreads whole (sequence, head) groups over the queues
+// (largest group first onto the least loaded queue, so tiles that read the same K/V run on
+// one XCD and share its L2), then orders each queue by decreasing cost so that the long
+// tail of a batch starts first and short items fill the gaps at the end.
+void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult, int tile_rows,
+                int step_rows, bool causal, bool key_major, int nq, HostPass &out)
+{
+    std::vector<Work> work;
+    std::vector<int64_t> group_cost;
+    for (int b = 0; b < B; b++) {
+        int32_t s = cu[b + 1] - cu[b];
+        if (s <= 0) continue;
+        int32_t nt = (int32_t)cdiv(s, tile_rows);
+        for (int h = 0; h < heads; h++) {
+            int32_t gid = (int32_t)group_cost.size();
+            int64_t gc = 0;
+            for (int32_t t = 0; t < nt; t++) {
+                int64_t cost;
+                if (!key_major) {
+                    // query tile t: keys 0 .. min(s, (t+1)*tile_rows) - 1 when causal
+                    int64_t keys = causal ? std::min<int64_t>(s, (int64_t)(t + 1) * tile_rows) : s;
+                    cost = cdiv(keys, step_rows);
+                } else {
+                    // key tile t: queries from the tile's first key to the end when causal
+                    int64_t first = causal ? (int64_t)t * tile_rows : 0;
+                    cost = cdiv(s - first, step_rows) * group_mult;
+                }
+                Work w;
+                w.it.seq_start = cu[b];
+                w.it.seq_len = s;
+                w.it.tile = t;
+                w.it.head = h;
+                w.cost = cost;
+                w.group = gid;
+                work.push_back(w);
+                gc += cost;
+            }
+            group_cost.push_back(gc);
+        }
+    }
+    // groups -> queues
+    std::vector<int32_t> order(group_cost.size());
+    for (size_t i = 0; i < order.size(); i++) order[i] = (int32_t)i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return group_cost[a] > group_cost[b]; });
+    std::vector<int64_t> load(nq, 0);
+    std::vector<int32_t> queue_of(group_cost.size(), 0);
+    for (int32_t g : order) {
+        int best = 0;
+        for (int x = 1; x < nq; x++)
+            if (load[x] < load[best]) best = x;
+        queue_of[g] = best;
+        load[best] += group_cost[g];
+    }
+    std::stable_sort(work.begin(), work.end(), [&](const Work &a, const Work &b) {
+        int qa = queue_of[a.group], qb = queue_of[b.group];
+        if (qa != qb) return qa < qb;
+        return a.cost > b.cost;
+    });
+    out.items.resize(work.size());
+    for (int x = 0; x <= kMaxQueues; x++) out.offsets[x] = (int64_t)work.size();
+    out.offsets[0] = 0;
+    int cur = 0;
+    for (size_t i = 0; i < work.size(); i++) {
+        out.items[i] = work[i].it;
+        int qx = queue_of[work[i].group];
+        while (cur < qx) out.offsets[++cur] = (int64_t)i;
+    }
+    while (cur < nq) out.offsets[++cur] = (int64_t)work.size();
+    out.tile_rows = tile_rows;
+}
+
+bool view_ok(const flexsp_tensor &t)
+{
+    if (!t.ptr) return false;
+    if (((uintptr_t)t.ptr & 15) != 0) return false;
+    if (t.stride_token <= 0 || t.stride_head <= 0) return false;
+    if ((t.stride_token % 8) != 0 || (t.stride_head % 8) != 0) return false;
+    return true;
+}
+
+int check_attn_common(flexsp_ctx *ctx, flexsp_plan *plan, const int32_t *cu_dev, int32_t head_begin,
+                      int32_t head_count, int32_t kv_head_begin, int32_t kv_head_count, int causal)
+{
+    if (!ctx || !plan || !cu_dev) return FLEXSP_INVALID_ARGUMENT;
+    if (plan->ctx != ctx) return FLEXSP_PLAN_MISMATCH;
+    if (head_begin < 0 || kv_head_begin < 0 || head_count <= 0 || kv_head_count <= 0)
+        return FLEXSP_INVALID_ARGUMENT;
+    if (head_count % kv_head_count != 0) return FLEXSP_INVALID_ARGUMENT;
+    if (head_count != plan->Hq || kv_head_count != plan->Hkv || (causal != 0) != (plan->causal != 0))
+        return FLEXSP_PLAN_MISMATCH;
+    if (ctx->device < 0 || !plan->dev_base) return FLEXSP_NO_DEVICE;
+    return FLEXSP_OK;
+}
+
+int grid_for(const flexsp_ctx *ctx, const HostPass &p, int per_cu)
+{
+    int64_t n = (int64_t)p.items.size();
+    int64_t g = (int64_t)ctx->num_cu * per_cu;
+    if (n < g) g = ((n + ctx->num_xcd - 1) / ctx->num_xcd) * ctx->num_xcd;
+    return (int)std::max<int64_t>(g, 1);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *flexsp_strerror(int status)
+{
+    switch (status) {
+    case FLEXSP_OK: return "ok";
+    case FLEXSP_INVALID_ARGUMENT: return "invalid argument";
+    case FLEXSP_UNSUPPORTED: return "unsupported configuration";
+    case FLEXSP_PLAN_MISMATCH: return "arguments do not match the plan";
+    case FLEXSP_HIP_ERROR: return "HIP runtime error";
+    case FLEXSP_OUT_OF_MEMORY: return "out of memory";
+    case FLEXSP_NO_DEVICE: return "no usable gfx950 device";
+    default: return "unknown status";
+    }
+}
+
+int flexsp_last_hip_error(void) { return g_last_hip_error; }
+
+const char *flexsp_version(void) { return "0.1"; }
+
+int flexsp_ctx_create(flexsp_ctx **out, int device)
+{
+    if (!out || device < -1) return FLEXSP_INVALID_ARGUMENT;
+    *out = nullptr;
+    flexsp_ctx *c = new (std::nothrow) flexsp_ctx;
+    if (!c) return FLEXSP_OUT_OF_MEMORY;
+    c->device = device;
+    c->num_cu = 0;
+    c->num_xcd = kMaxQueues;
+    c->profiling = false;
+    c->events_used = 0;
+    c->dropped = 0;
+    if (device >= 0) {
+        int n = 0;
+        hipError_t e = hipGetDeviceCount(&n);
+        if (e != hipSuccess || device >= n) {
+            delete c;
+            g_last_hip_error = (int)e;
+            return FLEXSP_NO_DEVICE;
+        }
+        hipDeviceProp_t pr;
+        e = hipGetDeviceProperties(&pr, device);
+        if (e != hipSuccess) {
+            delete c;
+            return hip_fail(e);
+        }
+        if (std::strncmp(pr.gcnArchName, "gfx950", 6) != 0) {
+            delete c;
+            return FLEXSP_NO_DEVICE;
+        }
+        c->num_cu = pr.multiProcessorCount;
+    }
+    *out = c;
+    return FLEXSP_OK;
+}
+
+void flexsp_ctx_destroy(flexsp_ctx *ctx)
+{
+    if (!ctx) return;
+    for (EventPair &e : ctx->events) {
+        (void)hipEventDestroy(e.start);
+        (void)hipEventDestroy(e.stop);
+    }
+    delete ctx;
+}
+
+int flexsp_profile_start(flexsp_ctx *ctx, int32_t max_launches)
+{
+    if (!ctx || max_launches <= 0) return FLEXSP_INVALID_ARGUMENT;
+    if (ctx->device < 0) return FLEXSP_NO_DEVICE;
+    try {
+        ctx->events.reserve((size_t)max_launches);
+    } catch (const std::bad_alloc &) {
+        return FLEXSP_OUT_OF_MEMORY;
+    }
+    while (ctx->events.size() < (size_t)max_launches) {
+        EventPair e;
+        e.kernel = 0;
+        hipError_t r = hipEventCreate(&e.start);
+        if (r != hipSuccess) return hip_fail(r);
+        r = hipEventCreate(&e.stop);
+        if (r != hipSuccess) {
+            (void)hipEventDestroy(e.start);
+            return hip_fail(r);
+        }
+        ctx->events.push_back(e);
+    }
+    ctx->events_used = 0;
+    ctx->dropped = 0;
+    ctx->profiling = true;
+    return FLEXSP_OK;
+}
+
+int flexsp_profile_stop(flexsp_ctx *ctx, flexsp_profile *out)
+{
+    if (!ctx || !out) return FLEXSP_INVALID_ARGUMENT;
+    if (ctx->device < 0) return FLEXSP_NO_DEVICE;
+    std::memset(out, 0, sizeof(*out));
+    ctx->profiling = false;
+    for (size_t i = 0; i < ctx->events_used; i++) {
+        EventPair &e = ctx->events[i];
+        hipError_t r = hipEventSynchronize(e.stop);
+        if (r != hipSuccess) return hip_fail(r);
+        float ms = 0.f;
+        r = hipEventElapsedTime(&ms, e.start, e.stop);
+        if (r != hipSuccess) return hip_fail(r);
+        out->ms[e.kernel] += ms;
+        out->launches[e.kernel]++;
+    }
+    out->dropped = ctx->dropped;
+    ctx->events_used = 0;
+    return FLEXSP_OK;
+}
+
+int flexsp_ctx_num_cu(const flexsp_ctx *ctx) { return ctx ? ctx->num_cu : 0; }
+int flexsp_ctx_num_xcd(const flexsp_ctx *ctx) { return ctx ? ctx->num_xcd : 0; }
+
+int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq, int32_t Hkv,
+                       int32_t D, int causal, flexsp_plan **out)
+{
+    if (!out) return FLEXSP_INVALID_ARGUMENT;
+    *out = nullptr;
+    if (!ctx || !cu || B < 0 || Hq <= 0 || Hkv <= 0 || D <= 0) return FLEXSP_INVALID_ARGUMENT;
+    if (Hq % Hkv != 0) return FLEXSP_INVALID_ARGUMENT;
+    if (cu[0] != 0) return FLEXSP_INVALID_ARGUMENT;
+    for (int b = 0; b < B; b++)
+        if (cu[b + 1] < cu[b]) return FLEXSP_INVALID_ARGUMENT;
+    if (D != 64 && D != 128) return FLEXSP_UNSUPPORTED;
+    flexsp_plan *p = new (std::nothrow) flexsp_plan;
+    if (!p) return FLEXSP_OUT_OF_MEMORY;
+    p->ctx = ctx;
+    p->B = B; p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->causal = causal ? 1 : 0;
+    p->T = cu[B];
+    p->dev_base = nullptr; p->dev_bytes = 0; p->delta = nullptr;
+    p->delta_bytes = (size_t)p->T * Hq * sizeof(float);
+    try {
+        p->cu.assign(cu, cu + B + 1);
+        int nq = ctx->num_xcd;
+        build_pass(p->cu, B, Hq, 1, kFwdBq, kFwdBk, causal != 0, false, nq, p->pass[FLEXSP_PASS_FWD]);
+        build_pass(p->cu, B, Hkv, Hq / Hkv, kDkvBk, kDkvBq, causal != 0, true, nq, p->pass[FLEXSP_PASS_BWD_DKV]);
+        build_pass(p->cu, B, Hq, 1, kDqBq, kDqBk, causal != 0, false, nq, p->pass[FLEXSP_PASS_BWD_DQ]);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return FLEXSP_OUT_OF_MEMORY;
+    }
+    for (int i = 0; i < 3; i++) std::memset(&p->dq[i], 0, sizeof(PassQueues));
+    if (ctx->device >= 0) {
+        // one allocation: [items x3][offsets x3][counters x3][delta]
+        int nq = ctx->num_xcd;
+        size_t off = 0, item_off[3], offs_off[3], ctr_off[3];
+        auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
+        for (int i = 0; i < 3; i++) {
+            item_off[i] = off;
+            off = align(off + p->pass[i].items.size() * sizeof(flexsp_item));
+        }
+        for (int i = 0; i < 3; i++) {
+            offs_off[i] = off;
+            off = align(off + (nq + 1) * sizeof(int32_t));
+        }
+        for (int i = 0; i < 3; i++) {
+            ctr_off[i] = off;
+            off = align(off + (nq + 1) * sizeof(int32_t));
+        }
+        size_t head_bytes = off;
+        size_t delta_off = off;
+        off = align(off + p->delta_bytes);
+        hipError_t e = hipSetDevice(ctx->device);
+        if (e == hipSuccess) e = hipMalloc(&p->dev_base, off ? off : 256);
+        if (e != hipSuccess) {
+            delete p;
+            return hip_fail(e);
+        }
+        p->dev_bytes = off;
+        std::vector<char> stage(head_bytes, 0);
+        for (int i = 0; i < 3; i++) {
+            if (!p->pass[i].items.empty())
+                std::memcpy(stage.data() + item_off[i], p->pass[i].items.data(),
+                            p->pass[i].items.size() * sizeof(flexsp_item));
+            int32_t *o = (int32_t *)(stage.data() + offs_off[i]);
+            for (int x = 0; x <= nq; x++) o[x] = (int32_t)p->pass[i].offsets[x];
+            p->dq[i].items = (const flexsp_item *)((char *)p->dev_base + item_off[i]);
+            p->dq[i].offsets = (const int32_t *)((char *)p->dev_base + offs_off[i]);
+            p->dq[i].counters = (int32_t *)((char *)p->dev_base + ctr_off[i]);
+            p->dq[i].nq = nq;
+        }
+        if (head_bytes) {
+            e = hipMemcpy(p->dev_base, stage.data(), head_bytes, hipMemcpyHostToDevice);
+            if (e != hipSuccess) {
+                (void)hipFree(p->dev_base);
+                delete p;
+                return hip_fail(e);
+            }
+        }
+        p->delta = (float *)((char *)p->dev_base + delta_off);
+    }
+    *out = p;
+    return FLEXSP_OK;
+}
+
+void flexsp_plan_destroy(flexsp_plan *plan)
+{
+    if (!plan) return;
+    if (plan->dev_base) (void)hipFree(plan->dev_base);
+    delete plan;
+}
+
+int64_t flexsp_plan_num_items(const flexsp_plan *plan, int pass)
+{
+    if (!plan || pass < 0 || pass > 2) return FLEXSP_INVALID_ARGUMENT;
+    return (int64_t)plan->pass[pass].items.size();
+}
+
+int flexsp_plan_get_items(const flexsp_plan *plan, int pass, flexsp_item *items, int64_t capacity,
+                          int64_t *queue_offsets)
+{
+    if (!plan || pass < 0 || pass > 2) return FLEXSP_INVALID_ARGUMENT;
+    const HostPass &hp = plan->pass[pass];
+    if (capacity < (int64_t)hp.items.size() || (!items && !hp.items.empty())) return FLEXSP_INVALID_ARGUMENT;
+    if (!hp.items.empty()) std::memcpy(items, hp.items.data(), hp.items.size() * sizeof(flexsp_item));
+    if (queue_offsets)
+        for (int x = 0; x <= plan->ctx->num_xcd; x++) queue_offsets[x] = hp.offsets[x];
+    return FLEXSP_OK;
+}
+
+int flexsp_plan_tile_rows(const flexsp_plan *plan, int pass)
+{
+    if (!plan || pass < 0 || pass > 2) return FLEXSP_INVALID_ARGUMENT;
+    return plan->pass[pass].tile_rows;
+}
+
+size_t flexsp_attn_bwd_workspace_bytes(const flexsp_plan *plan) { return plan ? plan->delta_bytes : 0; }
+
+static int permute_entry(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_t H, int32_t D,
+                         int32_t P, int32_t eb, flexsp_stream stream, bool unpack)
+{
+    if (T < 0 || H <= 0 || D <= 0 || P <= 0 || eb <= 0) return FLEXSP_INVALID_ARGUMENT;
+    if (H % P != 0) return FLEXSP_INVALID_ARGUMENT;
+    if (eb != 1 && eb != 2 && eb != 4 && eb != 8 && eb != 16) return FLEXSP_UNSUPPORTED;
+    if (!ctx) return FLEXSP_INVALID_ARGUMENT;
+    if (T == 0) return FLEXSP_OK;
+    if (!src || !dst) return FLEXSP_INVALID_ARGUMENT;
+    int64_t bytes = T * H * D * eb;
+    const char *s = (const char *)src;
+    const char *d = (const char *)dst;
+    if (s < d + bytes && d < s + bytes) return FLEXSP_INVALID_ARGUMENT;  // overlap
+    if (((uintptr_t)src | (uintptr_t)dst) % (uintptr_t)eb) return FLEXSP_INVALID_ARGUMENT;
+    if (ctx->device < 0) return FLEXSP_NO_DEVICE;
+    hipError_t e;
+    {
+        Timed tm(ctx, unpack ? FLEXSP_K_UNPACK : FLEXSP_K_PACK, (hipStream_t)stream);
+        e = launch_pack(src, dst, T, H, D, P, eb, unpack, (hipStream_t)stream);
+    }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
+int flexsp_pack(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_t H, int32_t D, int32_t P,
+                int32_t eb, flexsp_stream stream)
+{
+    return permute_entry(ctx, src, dst, T, H, D, P, eb, stream, false);
+}
+
+int flexsp_unpack(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_t H, int32_t D, int32_t P,
+                  int32_t eb, flexsp_stream stream)
+{
+    return permute_entry(ctx, src, dst, T, H, D, P, eb, stream, true);
+}
+
+int flexsp_attn_varlen_fwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                           flexsp_tensor v, const int32_t *cu_dev, int32_t head_begin, int32_t head_count,
+                           int32_t kv_head_begin, int32_t kv_head_count, int causal, float scale,
+                           flexsp_tensor o, float *lse, flexsp_stream stream)
+{
+    int rc = check_attn_common(ctx, plan, cu_dev, head_begin, head_count, kv_head_begin, kv_head_count, causal);
+    if (rc == FLEXSP_NO_DEVICE) {
+        // still report bad views first, so host-only tests can see them
+        if (!view_ok(q) || !view_ok(k) || !view_ok(v) || !view_ok(o) || !lse) return FLEXSP_INVALID_ARGUMENT;
+        return rc;
+    }
+    if (rc) return rc;
+    if (!view_ok(q) || !view_ok(k) || !view_ok(v) || !view_ok(o) || !lse) return FLEXSP_INVALID_ARGUMENT;
+    if (!std::isfinite(scale)) return FLEXSP_INVALID_ARGUMENT;
+    if (plan->pass[FLEXSP_PASS_FWD].items.empty()) return FLEXSP_OK;
+    if (scale <= 0.f) scale = 1.0f / std::sqrt((float)plan->D);
+    AttnArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.q = (const uint16_t *)q.ptr + (int64_t)head_begin * q.stride_head;
+    a.k = (const uint16_t *)k.ptr + (int64_t)kv_head_begin * k.stride_head;
+    a.v = (const uint16_t *)v.ptr + (int64_t)kv_head_begin * v.stride_head;
+    a.out_o = (uint16_t *)o.ptr + (int64_t)head_begin * o.stride_head;
+    a.q_st = q.stride_token; a.q_sh = q.stride_head;
+    a.k_st = k.stride_token; a.k_sh = k.stride_head;
+    a.v_st = v.stride_token; a.v_sh = v.stride_head;
+    a.o_st = o.stride_token; a.o_sh = o.stride_head;
+    a.lse_out = lse;
+    a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
+    a.scale = scale; a.scale_l2 = scale * 1.4426950408889634f;
+    a.pq = plan->dq[FLEXSP_PASS_FWD];
+    hipError_t e;
+    {
+        Timed tm(ctx, FLEXSP_K_FWD, (hipStream_t)stream);
+        e = launch_attn_fwd(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_FWD], 2), (hipStream_t)stream);
+    }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
+int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                           flexsp_tensor v, flexsp_tensor o, flexsp_tensor dO, const float *lse,
+                           const int32_t *cu_dev, int32_t head_begin, int32_t head_count,
+                           int32_t kv_head_begin, int32_t kv_head_count, int causal, float scale,
+                           flexsp_tensor dq, flexsp_tensor dk, flexsp_tensor dv, int32_t grad_dtype,
+                           flexsp_stream stream)
+{
+    int rc = check_attn_common(ctx, plan, cu_dev, head_begin, head_count, kv_head_begin, kv_head_count, causal);
+    bool views = view_ok(q) && view_ok(k) && view_ok(v) && view_ok(o) && view_ok(dO) && view_ok(dq) &&
+                 view_ok(dk) && view_ok(dv) && lse;
+    if (rc == FLEXSP_NO_DEVICE && !views) return FLEXSP_INVALID_ARGUMENT;
+    if ((rc == FLEXSP_OK || rc == FLEXSP_NO_DEVICE) && grad_dtype != FLEXSP_BF16 && grad_dtype != FLEXSP_F32)
+        return FLEXSP_UNSUPPORTED;
+    if (rc) return rc;
+    if (!views || !std::isfinite(scale)) return FLEXSP_INVALID_ARGUMENT;
+    if (plan->pass[FLEXSP_PASS_FWD].items.empty()) return FLEXSP_OK;
+    if (scale <= 0.f) scale = 1.0f / std::sqrt((float)plan->D);
+    AttnArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.q = (const uint16_t *)q.ptr + (int64_t)head_begin * q.stride_head;
+    a.k = (const uint16_t *)k.ptr + (int64_t)kv_head_begin * k.stride_head;
+    a.v = (const uint16_t *)v.ptr + (int64_t)kv_head_begin * v.stride_head;
+    a.o = (const uint16_t *)o.ptr + (int64_t)head_begin * o.stride_head;
+    a.dO = (const uint16_t *)dO.ptr + (int64_t)head_begin * dO.stride_head;
+    const int64_t gb = grad_dtype == FLEXSP_F32 ? 4 : 2;
+    a.grad_f32 = grad_dtype == FLEXSP_F32;
+    a.dq = (char *)dq.ptr + (int64_t)head_begin * dq.stride_head * gb;
+    a.dk = (char *)dk.ptr + (int64_t)kv_head_begin * dk.stride_head * gb;
+    a.dv = (char *)dv.ptr + (int64_t)kv_head_begin * dv.stride_head * gb;
+    a.q_st = q.stride_token; a.q_sh = q.stride_head;
+    a.k_st = k.stride_token; a.k_sh = k.stride_head;
+    a.v_st = v.stride_token; a.v_sh = v.stride_head;
+    a.o_st = o.stride_token; a.o_sh = o.stride_head;
+    a.do_st = dO.stride_token; a.do_sh = dO.stride_head;
+    a.dq_st = dq.stride_token; a.dq_sh = dq.stride_head;
+    a.dk_st = dk.stride_token; a.dk_sh = dk.stride_head;
+    a.dv_st = dv.stride_token; a.dv_sh = dv.stride_head;
+    a.lse_in = lse;
+    a.delta_out = plan->delta;
+    a.delta_in = plan->delta;
+    a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
+    a.scale = scale; a.scale_l2 = scale * 1.4426950408889634f;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    {
+        Timed tm(ctx, FLEXSP_K_BWD_DELTA, s);
+        e = launch_attn_bwd_delta(a, plan->D, s);
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    a.pq = plan->dq[FLEXSP_PASS_BWD_DKV];
+    {
+        Timed tm(ctx, FLEXSP_K_BWD_DKV, s);
+        e = launch_attn_bwd_dkv(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DKV], 1), s);
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    a.pq = plan->dq[FLEXSP_PASS_BWD_DQ];
+    {
+        Timed tm(ctx, FLEXSP_K_BWD_DQ, s);
+        e = launch_attn_bwd_dq(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DQ], 2), s);
+    }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
+}  // extern "C"

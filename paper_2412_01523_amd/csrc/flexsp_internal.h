@@ -1,0 +1,57 @@
+// Internal declarations shared by the host code and the kernels of libflexsp.
+// Nothing here is part of the public ABI (see include/flexsp.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "flexsp.h"
+
+namespace flexsp {
+
+// Tile shapes.  The plan builder and the kernels must agree on these.
+constexpr int kFwdBq = 128;    // query rows per forward work item (4 waves x 32 rows)
+constexpr int kFwdBk = 64;     // key rows staged in LDS per forward step
+constexpr int kDqBq = 128;     // query rows per dQ work item
+constexpr int kDqBk = 64;      // key rows per dQ step
+constexpr int kDkvBk = 128;    // key rows per dK/dV work item (4 waves x 32 rows)
+constexpr int kDkvBq = 64;     // query rows per dK/dV step
+constexpr int kThreads = 256;  // every attention kernel runs 4 wavefronts per workgroup
+constexpr int kMaxQueues = 8;  // one work queue per XCD
+
+struct PassQueues {
+    const flexsp_item *items;  // device, all queues back to back
+    const int32_t *offsets;    // device, nq + 1 boundaries into items
+    int32_t *counters;         // device, nq fetch counters + 1 "workgroups done" counter
+    int32_t nq;
+};
+
+// Arguments of the attention kernels.  Strides are in elements; pointers already include
+// the first head of the subset.
+struct AttnArgs {
+    const uint16_t *q, *k, *v, *o, *dO;
+    uint16_t *out_o;
+    void *dq, *dk, *dv;  // bf16 or fp32 elements, see grad_f32
+    const float *lse_in, *delta_in;
+    float *lse_out, *delta_out;
+    int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh;
+    int64_t dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
+    int32_t T;       // tokens in the packed stream (row length of lse / delta)
+    int32_t Hq;      // query heads in the subset
+    int32_t G;       // query heads per kv head
+    int32_t causal;
+    int32_t grad_f32;  // gradients are stored as fp32 instead of bf16
+    float scale;     // softmax scale
+    float scale_l2;  // scale * log2(e)
+    PassQueues pq;
+};
+
+// Launchers implemented next to their kernels.  All are asynchronous on `s`.
+hipError_t launch_pack(const void *src, void *dst, int64_t T, int H, int D, int P, int eb,
+                       bool unpack, hipStream_t s);
+hipError_t launch_attn_fwd(const AttnArgs &a, int D, int grid, hipStream_t s);
+hipError_t launch_attn_bwd_delta(const AttnArgs &a, int D, hipStream_t s);
+hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s);
+hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s);
+
+}  // namespace flexsp

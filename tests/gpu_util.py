@@ -1,0 +1,79 @@
+"""Helpers for the GPU parity tests: host<->device marshalling and the error metrics."""
+import numpy as np
+
+MAX_ABS = 2e-2      # tolerance on max |gpu - oracle| per tensor (bf16 inputs)
+REL_L2 = 5e-3       # tolerance on ||gpu - oracle||_2 / ||oracle||_2 per tensor
+
+
+def to_dev(bits):
+    """uint16 bf16 bit patterns -> torch.bfloat16 tensor on cuda:0 (same bits)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def to_bits(t):
+    """torch bf16 tensor -> uint16 bit patterns on the host."""
+    import torch
+    return t.detach().contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def bf16_f64(bits):
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def errors(gpu_f64, ref_f64):
+    d = gpu_f64 - ref_f64
+    max_abs = float(np.abs(d).max()) if d.size else 0.0
+    den = float(np.sqrt((ref_f64 ** 2).sum()))
+    rel = float(np.sqrt((d ** 2).sum()) / den) if den > 0 else float(np.sqrt((d ** 2).sum()))
+    return max_abs, rel
+
+
+def bf16_store_tol(ref_f64):
+    """max-abs tolerance for a result that is ROUNDED TO bf16 at the end: the stated 2e-2, or half
+    a bf16 ulp of the largest reference value (2^-8 relative) where that alone is larger, which
+    happens once |value| >= 5.12 (grouped-query sums of dK/dV reach that)."""
+    return max(MAX_ABS, 2.0 ** -8 * float(np.abs(ref_f64).max()))
+
+
+def assert_close(name, gpu_f64, ref_f64, max_abs=MAX_ABS, rel_l2=REL_L2):
+    assert np.isfinite(gpu_f64).all(), f"{name}: non-finite values"
+    ma, rl = errors(gpu_f64, ref_f64)
+    assert ma <= max_abs and rl <= rel_l2, f"{name}: max_abs={ma:.3e} (tol {max_abs}) rel_l2={rl:.3e} (tol {rel_l2})"
+    return ma, rl
+
+
+class GpuAttn:
+    """Runs the HIP path (through the C ABI) on host bf16 bit patterns."""
+
+    def __init__(self, ctx):
+        self.ctx = ctx
+
+    def run(self, q, k, v, dO, cu, causal=True, scale=0.0, backward=True, grad_f32=False):
+        import torch
+        from paper_2412_01523_amd import binding as fx
+        T, Hq, D = q.shape
+        Hkv = k.shape[1]
+        plan = fx.Plan(self.ctx, cu, Hq, Hkv, D, causal)
+        dq_, dk_, dv_ = to_dev(q), to_dev(k), to_dev(v)
+        cu_d = torch.from_numpy(np.ascontiguousarray(cu, dtype=np.int32)).cuda()
+        o = torch.full((T, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lse = torch.full((Hq, T), float("nan"), dtype=torch.float32, device="cuda")
+        fx.flexsp_attn_varlen_fwd(self.ctx, plan, dq_, dk_, dv_, cu_d, o, lse, causal=causal, softmax_scale=scale)
+        out = {"O": to_bits(o), "LSE": lse.cpu().numpy().astype(np.float64)}
+        if backward:
+            g = to_dev(dO)
+            gdt = torch.float32 if grad_f32 else torch.bfloat16
+            gq = torch.full((T, Hq, D), float("nan"), dtype=gdt, device="cuda")
+            gk = torch.full((T, Hkv, D), float("nan"), dtype=gdt, device="cuda")
+            gv = torch.full((T, Hkv, D), float("nan"), dtype=gdt, device="cuda")
+            fx.flexsp_attn_varlen_bwd(self.ctx, plan, dq_, dk_, dv_, o, g, lse, cu_d, gq, gk, gv,
+                                      causal=causal, softmax_scale=scale)
+            if grad_f32:
+                out.update(dQ=gq.cpu().numpy().astype(np.float64), dK=gk.cpu().numpy().astype(np.float64),
+                           dV=gv.cpu().numpy().astype(np.float64))
+            else:
+                out.update(dQ=bf16_f64(to_bits(gq)), dK=bf16_f64(to_bits(gk)), dV=bf16_f64(to_bits(gv)))
+        torch.cuda.synchronize()
+        plan.close()
+        return out

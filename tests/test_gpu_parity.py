@@ -1,0 +1,217 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU fp64 oracle on
+the same seeded inputs.  Tolerances (bf16 inputs): max-abs 2e-2, relative L2 5e-3 per tensor
+for O, dQ, dK, dV; LSE additionally within 1e-3.  pack/unpack: bit-exact."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2412_01523_amd import workloads as wl
+
+from gpu_util import MAX_ABS, GpuAttn, assert_close, bf16_f64, bf16_store_tol, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2412_01523_amd import binding as fx
+    c = fx.Context(0)
+    assert c.num_cu > 0
+    yield c
+    c.close()
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+# ----------------------------------------------------------------------------- permute
+PERMUTE_CASES = [
+    # T, H, D, P, numpy dtype
+    (436, 8, 64, 4, np.uint16),
+    (1000, 32, 128, 8, np.uint16),      # 1 KiB runs, several tiles, ragged tail
+    (777, 6, 40, 3, np.uint16),         # run = 160 B
+    (333, 4, 5, 2, np.uint16),          # run = 20 B: 4-byte vectors
+    (129, 3, 7, 3, np.uint16),          # run = 14 B: 2-byte vectors
+    (65, 2, 3, 2, np.uint8),            # run = 3 B: byte path
+    (257, 8, 16, 8, np.uint32),
+    (64, 4, 8, 1, np.uint16),           # P = 1: identity
+    (0, 4, 8, 2, np.uint16),            # empty
+    (1, 16, 128, 16, np.uint16),        # one token
+]
+
+
+@pytest.mark.parametrize("T,H,D,P,dt", PERMUTE_CASES)
+def test_pack_unpack_bit_exact(ctx, T, H, D, P, dt):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    say(f"permute case T={T} H={H} D={D} P={P} dtype={np.dtype(dt).name}")
+    n = T * H * D
+    rng = np.random.Generator(np.random.Philox(key=[77, T + H]))
+    x = rng.integers(0, np.iinfo(dt).max, size=n, dtype=dt, endpoint=True).reshape(T, H, D)
+    tdt = {np.uint16: torch.int16, np.uint8: torch.uint8, np.uint32: torch.int32}[dt]
+    sdt = {np.uint16: np.int16, np.uint8: np.uint8, np.uint32: np.int32}[dt]
+    xd = torch.from_numpy(x.view(sdt)).cuda()
+    yd = torch.full((P, T, H // P, D), 0x55, dtype=tdt, device="cuda")
+    fx.flexsp_pack(ctx, xd, yd, P)
+    want = oracle.pack(x, P)
+    got = yd.cpu().numpy().view(dt)
+    assert np.array_equal(got, want)
+    zd = torch.full((T, H, D), 0x33, dtype=tdt, device="cuda")
+    fx.flexsp_unpack(ctx, yd, zd)
+    assert np.array_equal(zd.cpu().numpy().view(dt), x)
+    assert np.array_equal(oracle.unpack(want), x)
+
+
+def test_pack_misaligned_base_uses_narrow_path(ctx):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    T, H, D, P = 100, 4, 64, 2
+    x = wl.index_pattern_u16((T * H * D + 1,))
+    buf = torch.from_numpy(x.view(np.int16)).cuda()
+    src = buf[1:].view(T, H, D)            # base is 2-byte aligned only
+    dst = torch.zeros((P, T, H // P, D), dtype=torch.int16, device="cuda")
+    fx.flexsp_pack(ctx, src, dst, P)
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), oracle.pack(x[1:].reshape(T, H, D), P))
+
+
+def test_pack_config1_full_size(ctx):
+    """[32768, 32, 128] bf16, P = 8 (the shape the bandwidth figure is quoted on)."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    cfg = wl.CONFIGS[1]
+    T, H, D, P = cfg.tokens, cfg.hq * cfg.sp_degree, cfg.d, cfg.sp_degree
+    x = wl.index_pattern_u16((T, H, D))
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    yd = torch.zeros((P, T, H // P, D), dtype=torch.int16, device="cuda")
+    fx.flexsp_pack(ctx, xd, yd, P)
+    got = yd.cpu().numpy().view(np.uint16)
+    for r in range(P):          # slab r = head group r made contiguous (index formula)
+        assert np.array_equal(got[r], x[:, r * (H // P):(r + 1) * (H // P), :])
+    zd = torch.zeros_like(xd)
+    fx.flexsp_unpack(ctx, yd, zd)
+    assert torch.equal(zd, xd)
+
+
+# ----------------------------------------------------------------------------- attention, small
+SMALL_CASES = [
+    # name, lens, Hq, Hkv, D, causal
+    ("cfg0", [17, 64, 100, 255], 4, 4, 64, True),
+    ("cfg0-d128", [17, 64, 100, 255], 4, 4, 128, True),
+    ("tile-edges", [1, 128, 129, 64, 65, 127, 1, 256, 257, 63], 2, 2, 128, True),
+    ("empty-seqs", [0, 5, 0, 0, 200, 0], 2, 2, 64, True),
+    ("gqa", [300, 31, 513], 8, 2, 128, True),
+    ("gqa-d64", [300, 31, 513], 4, 1, 64, True),
+    ("noncausal", [17, 64, 100, 255, 130], 2, 2, 128, False),
+    ("noncausal-gqa-d64", [70, 129, 1], 4, 2, 64, False),
+    ("several-tiles", [1500, 700], 2, 2, 128, True),
+]
+
+
+@pytest.mark.parametrize("name,lens,Hq,Hkv,D,causal", SMALL_CASES, ids=[c[0] for c in SMALL_CASES])
+def test_attention_matches_oracle_elementwise(ctx, name, lens, Hq, Hkv, D, causal):
+    say(f"attention case {name} lens={lens} Hq={Hq} Hkv={Hkv} D={D} causal={causal}")
+    T = sum(lens)
+    cu = wl.cu_seqlens(lens)
+    seed = 4242 + len(name)
+    q = wl.normal_bf16(seed, wl.TID_Q, (T, Hq, D))
+    k = wl.normal_bf16(seed, wl.TID_K, (T, Hkv, D))
+    v = wl.normal_bf16(seed, wl.TID_V, (T, Hkv, D))
+    g = wl.normal_bf16(seed, wl.TID_DO, (T, Hq, D))
+    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, causal)
+    ref = {"dQ": dQ, "dK": dK, "dV": dV}
+    for grad_f32 in (False, True):
+        out = GpuAttn(ctx).run(q, k, v, g, cu, causal, grad_f32=grad_f32)
+        res = {}
+        res["O"] = assert_close("O", bf16_f64(out["O"]), O)
+        assert np.abs(out["LSE"] - LSE).max() < 1e-3, "LSE"
+        for name in ("dQ", "dK", "dV"):
+            # fp32 gradients and single-head-group bf16 gradients: the stated 2e-2.  bf16 gradients
+            # summed over a query-head group: 2e-2 or half a bf16 ulp of the largest value.
+            tol = MAX_ABS if (grad_f32 or Hq == Hkv) else bf16_store_tol(ref[name])
+            res[name] = assert_close(name, out[name], ref[name], max_abs=tol)
+        say(f"  grad_f32={grad_f32} errors (max_abs, rel_l2): " +
+            " ".join(f"{k_}=({a:.2e},{b:.2e})" for k_, (a, b) in res.items()))
+
+
+def test_explicit_scale_and_plan_reuse_and_determinism(ctx):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    lens = [200, 77, 333]
+    T, Hq, Hkv, D = sum(lens), 4, 2, 128
+    cu = wl.cu_seqlens(lens)
+    q, k, v, g = (wl.normal_bf16(99, i, (T, h, D)) for i, h in ((0, Hq), (1, Hkv), (2, Hkv), (3, Hq)))
+    scale = 0.05
+    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, True, scale)
+    plan = fx.Plan(ctx, cu, Hq, Hkv, D, True)
+    qd, kd, vd, gd = to_dev(q), to_dev(k), to_dev(v), to_dev(g)
+    cud = torch.from_numpy(cu).cuda()
+    outs = []
+    for rep in range(3):                       # the same plan serves every layer's fwd and bwd
+        o = torch.zeros((T, Hq, D), dtype=torch.bfloat16, device="cuda")
+        lse = torch.zeros((Hq, T), dtype=torch.float32, device="cuda")
+        fx.flexsp_attn_varlen_fwd(ctx, plan, qd, kd, vd, cud, o, lse, softmax_scale=scale)
+        gq, gk, gv = torch.zeros_like(qd), torch.zeros_like(kd), torch.zeros_like(vd)
+        fx.flexsp_attn_varlen_bwd(ctx, plan, qd, kd, vd, o, gd, lse, cud, gq, gk, gv, softmax_scale=scale)
+        torch.cuda.synchronize()
+        outs.append([to_bits(o), lse.cpu().numpy(), to_bits(gq), to_bits(gk), to_bits(gv)])
+    for rep in (1, 2):                         # no atomics on floats: bitwise reproducible
+        for a, b in zip(outs[0], outs[rep]):
+            assert np.array_equal(a, b)
+    assert_close("O", bf16_f64(outs[0][0]), O)
+    assert_close("dQ", bf16_f64(outs[0][2]), dQ)
+    assert_close("dK", bf16_f64(outs[0][3]), dK)
+    assert_close("dV", bf16_f64(outs[0][4]), dV)
+    plan.close()
+
+
+def test_heads_subset_of_a_strided_tensor(ctx):
+    """q/k/v/o given as views into the sequence-sharded [T, H_tot, D] tensors: heads 8..11 of 16."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    lens = [150, 90]
+    T, Htot, D, hb, hc = sum(lens), 16, 128, 8, 4
+    cu = wl.cu_seqlens(lens)
+    q, k, v, g = (wl.normal_bf16(31, i, (T, Htot, D)) for i in range(4))
+    sl = slice(hb, hb + hc)
+    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q[:, sl], k[:, sl], v[:, sl], g[:, sl], cu, True)
+    plan = fx.Plan(ctx, cu, hc, hc, D, True)
+    qd, kd, vd, gd = to_dev(q), to_dev(k), to_dev(v), to_dev(g)
+    cud = torch.from_numpy(cu).cuda()
+    o = torch.zeros((T, Htot, D), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((hc, T), dtype=torch.float32, device="cuda")
+    fx.flexsp_attn_varlen_fwd(ctx, plan, qd, kd, vd, cud, o, lse, head_begin=hb, kv_head_begin=hb)
+    gq, gk, gv = torch.zeros_like(qd), torch.zeros_like(kd), torch.zeros_like(vd)
+    fx.flexsp_attn_varlen_bwd(ctx, plan, qd, kd, vd, o, gd, lse, cud, gq, gk, gv, head_begin=hb, kv_head_begin=hb)
+    torch.cuda.synchronize()
+    ob = to_bits(o)
+    assert_close("O", bf16_f64(ob[:, sl]), O)
+    assert not ob[:, :hb].any() and not ob[:, hb + hc:].any()       # other heads untouched
+    for name, t, ref in (("dQ", gq, dQ), ("dK", gk, dK), ("dV", gv, dV)):
+        b = to_bits(t)
+        assert_close(name, bf16_f64(b[:, sl]), ref)
+        assert not b[:, :hb].any() and not b[:, hb + hc:].any()
+    plan.close()
+
+
+def test_error_paths_do_not_launch(ctx):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    cu = wl.cu_seqlens([64])
+    plan = fx.Plan(ctx, cu, 2, 2, 64, True)
+    t = torch.zeros((64, 2, 64), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((2, 64), dtype=torch.float32, device="cuda")
+    cud = torch.from_numpy(cu).cuda()
+    with pytest.raises(fx.FlexspError) as e:
+        fx.flexsp_attn_varlen_fwd(ctx, plan, t, t, t, cud, t, lse, head_count=4)
+    assert e.value.status == fx.PLAN_MISMATCH
+    with pytest.raises(fx.FlexspError) as e:
+        fx.flexsp_attn_varlen_fwd(ctx, plan, t, t, t, cud, t, lse, causal=False)
+    assert e.value.status == fx.PLAN_MISMATCH
+    with pytest.raises(fx.FlexspError) as e:
+        fx.flexsp_pack(ctx, t, t, 2)                     # src and dst overlap
+    assert e.value.status == fx.INVALID_ARGUMENT
+    plan.close()

@@ -1,0 +1,144 @@
+"""CPU-only tests of the C-ABI library's host logic: it loads, exports every declared symbol,
+validates arguments before any launch, and builds longest-first tile plans."""
+import ctypes
+import re
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+from paper_2412_01523_amd import binding as fx
+from paper_2412_01523_amd import workloads as wl
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def test_library_exports_every_declared_symbol():
+    header = (ROOT / "include" / "flexsp.h").read_text()
+    declared = set(re.findall(r"\b(flexsp_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(fx.EXPORTS)
+    L = fx.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert fx.lib().flexsp_version().decode() == "0.1"
+    assert fx.lib().flexsp_strerror(fx.PLAN_MISMATCH).decode() == "arguments do not match the plan"
+
+
+@pytest.fixture(scope="module")
+def host_ctx():
+    c = fx.Context(-1)
+    yield c
+    c.close()
+
+
+def test_host_only_context_and_bad_devices(host_ctx):
+    assert host_ctx.num_cu == 0 and host_ctx.num_xcd == 8
+    with pytest.raises(fx.FlexspError) as e:
+        fx.Context(-2)
+    assert e.value.status == fx.INVALID_ARGUMENT
+
+
+def test_plan_argument_validation(host_ctx):
+    ok = np.array([0, 5, 9], dtype=np.int32)
+    for cu, hq, hkv, d, status in [
+        (np.array([1, 5], dtype=np.int32), 2, 2, 64, fx.INVALID_ARGUMENT),      # cu[0] != 0
+        (np.array([0, 5, 4], dtype=np.int32), 2, 2, 64, fx.INVALID_ARGUMENT),   # decreasing
+        (ok, 3, 2, 64, fx.INVALID_ARGUMENT),                                     # Hq % Hkv
+        (ok, 0, 1, 64, fx.INVALID_ARGUMENT),
+        (ok, 2, 2, 96, fx.UNSUPPORTED),                                          # head dim
+    ]:
+        with pytest.raises(fx.FlexspError) as e:
+            fx.Plan(host_ctx, cu, hq, hkv, d)
+        assert e.value.status == status
+
+
+def _check_pass(plan, which, lens, heads, rows):
+    items, offs = plan.items(which)
+    cu = wl.cu_seqlens(lens)
+    # every (sequence, tile, head) exactly once
+    want = set()
+    for b, s in enumerate(lens):
+        for t in range(-(-s // rows)):
+            for h in range(heads):
+                want.add((int(cu[b]), s, t, h))
+    got = [tuple(int(x) for x in it) for it in items]
+    assert len(got) == len(set(got)) == len(want) and set(got) == want
+    assert offs[0] == 0 and offs[-1] == len(got) and (np.diff(offs) >= 0).all()
+    return items, offs
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_plan_covers_every_tile_once_longest_first(host_ctx, causal):
+    lens = [17, 64, 0, 100, 255, 1000, 129, 4000]
+    hq, hkv, d = 4, 2, 128
+    plan = fx.Plan(host_ctx, wl.cu_seqlens(lens), hq, hkv, d, causal)
+    live = [s for s in lens if s > 0]
+    for which, heads in ((fx.PASS_FWD, hq), (fx.PASS_BWD_DKV, hkv), (fx.PASS_BWD_DQ, hq)):
+        rows = plan.tile_rows(which)
+        items, offs = _check_pass(plan, which, live if False else lens, heads, rows)
+        # inside a queue: cost never increases.  cost of a query tile = keys it reads;
+        # of a key tile = query rows that read it.
+        for x in range(len(offs) - 1):
+            seg = items[offs[x]:offs[x + 1]]
+            if which == fx.PASS_BWD_DKV:
+                cost = [(int(i["seq_len"]) - (int(i["tile"]) * rows if causal else 0)) for i in seg]
+                step = 64
+            else:
+                cost = [min(int(i["seq_len"]), (int(i["tile"]) + 1) * rows) if causal else int(i["seq_len"]) for i in seg]
+                step = 64
+            steps = [-(-c // step) for c in cost]
+            assert all(a >= b for a, b in zip(steps, steps[1:]))
+            # a (sequence, head) group lives in exactly one queue
+        owner = {}
+        for x in range(len(offs) - 1):
+            for i in items[offs[x]:offs[x + 1]]:
+                key = (int(i["seq_start"]), int(i["head"]))
+                assert owner.setdefault(key, x) == x
+    assert plan.workspace_bytes == sum(lens) * hq * 4
+    plan.close()
+
+
+def test_plan_balances_queues_on_the_long_tail_config(host_ctx):
+    cfg = wl.CONFIGS[2]
+    lens = wl.lengths(cfg)
+    plan = fx.Plan(host_ctx, wl.cu_seqlens(lens), cfg.hq, cfg.hkv, cfg.d, True)
+    items, offs = plan.items(fx.PASS_FWD)
+    rows = plan.tile_rows(fx.PASS_FWD)
+    load = []
+    for x in range(8):
+        seg = items[offs[x]:offs[x + 1]]
+        load.append(sum(-(-min(int(i["seq_len"]), (int(i["tile"]) + 1) * rows) // 64) for i in seg))
+    assert max(load) <= 1.05 * (sum(load) / 8)
+    # the very first item of each queue is one of the longest tiles of the batch
+    longest = max(lens)
+    assert all(int(items[offs[x]]["seq_len"]) >= 0.2 * longest for x in range(8))
+    plan.close()
+
+
+def test_permute_and_attention_validation_without_a_device(host_ctx):
+    L = fx.lib()
+    h = host_ctx.handle
+    buf = (ctypes.c_char * 4096)()
+    a = ctypes.addressof(buf)
+    # shape errors come first, whatever the pointers are
+    assert L.flexsp_pack(h, a, a + 2048, 4, 6, 8, 4, 2, None) == fx.INVALID_ARGUMENT    # H % P
+    assert L.flexsp_pack(h, a, a + 2048, 4, 4, 8, 2, 3, None) == fx.UNSUPPORTED         # elem size
+    assert L.flexsp_pack(h, a, a + 2048, -1, 4, 8, 2, 2, None) == fx.INVALID_ARGUMENT
+    assert L.flexsp_pack(None, a, a + 2048, 4, 4, 8, 2, 2, None) == fx.INVALID_ARGUMENT
+    assert L.flexsp_pack(h, None, a, 4, 4, 8, 2, 2, None) == fx.INVALID_ARGUMENT
+    assert L.flexsp_pack(h, a, a + 64, 4, 4, 8, 2, 2, None) == fx.INVALID_ARGUMENT      # overlap
+    assert L.flexsp_unpack(h, a, a + 2048, 0, 4, 8, 2, 2, None) == fx.OK                # empty: no-op
+    # well-formed call on a host-only context: refuses to launch, does not crash
+    assert L.flexsp_pack(h, a, a + 2048, 4, 4, 8, 2, 2, None) == fx.NO_DEVICE
+    plan = fx.Plan(host_ctx, np.array([0, 8], dtype=np.int32), 2, 2, 64, True)
+    t = fx.Tensor(a, 128, 64)
+    bad = fx.Tensor(a + 2, 128, 64)                                                      # misaligned
+    lse = a + 2048
+    f = L.flexsp_attn_varlen_fwd
+    assert f(h, plan.handle, t, t, t, a, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.NO_DEVICE
+    assert f(h, plan.handle, bad, t, t, a, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.INVALID_ARGUMENT
+    assert f(h, plan.handle, t, t, t, a, 0, 4, 0, 2, 1, 0.0, t, lse, None) == fx.PLAN_MISMATCH
+    assert f(h, plan.handle, t, t, t, a, 0, 2, 0, 2, 0, 0.0, t, lse, None) == fx.PLAN_MISMATCH
+    assert f(h, plan.handle, t, t, t, None, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.INVALID_ARGUMENT
+    assert f(h, None, t, t, t, a, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.INVALID_ARGUMENT
+    plan.close()

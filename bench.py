@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the one-GPU hot path: layout permute + packed causal attention fwd + bwd.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One STEP is one pass of the whole path for one micro-batch of one attention layer on one GPU
+of an SP group of degree P (paper Sec. 2.1.2, Eq. 2-4 and their backward):
+
+    plan (host lengths -> tile queues) ->
+    pack q, k, v   [T/P, P*Hp, D] -> per-peer slabs            (local half of Eq. 2)
+    attention forward on [T, Hp, D]                            (Eq. 3)
+    unpack o       slabs -> [T/P, P*Hp, D]                     (local half of Eq. 4)
+    pack dO ; attention backward ; unpack dq, dk, dv           (the same exchanges, backward)
+
+The wire exchange itself is out of scope (one GPU): the slabs a GPU packs are fed to its own
+attention as if they were what the peers sent, which has the same shapes and byte counts.
+
+Prints ONE JSON line.  `value` = causal-effective attention FLOPs (14*D*Hq*sum_b s_b(s_b+1)/2)
+per second over the whole step, inputs resident in HBM.  `roofline` describes the dominant
+kernel, timed with HIP events recorded by the library around each of its launches on the
+stream they run on.  `cpu_baseline` times the CPU fp64 oracle on a bounded sample of the same
+workload (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK = 2.5e15     # MI355X dense bf16 MFMA, FLOP/s (256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz)
+HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="pareto-64k",
+                    help="lognormal-32k | pareto-64k | single-128k | bimodal-256k-gqa | tiny-436")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-permute-leg", action="store_true")
+    ap.add_argument("--attention-only", action="store_true", help="step = plan + fwd + bwd (no permutes)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    from paper_2412_01523_amd import workloads as wl
+
+    cfg = next(c for c in wl.CONFIGS if c.name == args.workload)
+    lens = wl.lengths(cfg)
+    cu = wl.cu_seqlens(lens)
+    T, Hq, Hkv, D = cfg.tokens, cfg.hq, cfg.hkv, cfg.d
+    P = cfg.sp_degree if cfg.sp_degree else 8
+    Tl = T // P
+    f_fwd, f_bwd = wl.attn_flops(lens, Hq, D, True)
+    pairs_heads = wl.causal_pairs(lens) * Hq
+
+    torch.cuda.set_device(0)
+    ctx = fx.Context(0)
+    dev = "cuda"
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    # sequence-sharded inputs of this GPU: T/P tokens x all heads (synthetic N(0,1), seeded)
+    xq = dev_bf16(wl.normal_bf16(cfg.seed, wl.TID_Q, (Tl, P * Hq, D)))
+    xk = dev_bf16(wl.normal_bf16(cfg.seed, wl.TID_K, (Tl, P * Hkv, D)))
+    xv = dev_bf16(wl.normal_bf16(cfg.seed, wl.TID_V, (Tl, P * Hkv, D)))
+    xg = dev_bf16(wl.normal_bf16(cfg.seed, wl.TID_DO, (Tl, P * Hq, D)))
+    # head-sharded slabs [P, T/P, Hp, D] == [T, Hp, D]
+    new = lambda h: torch.empty((P, Tl, h, D), dtype=torch.bfloat16, device=dev)
+    sq, sk, sv, sg, so = new(Hq), new(Hkv), new(Hkv), new(Hq), new(Hq)
+    sdq, sdk, sdv = new(Hq), new(Hkv), new(Hkv)
+    yo, ydq = torch.empty_like(xq), torch.empty_like(xq)
+    ydk, ydv = torch.empty_like(xk), torch.empty_like(xv)
+    lse = torch.empty((Hq, T), dtype=torch.float32, device=dev)
+    cud = torch.from_numpy(cu).to(dev)
+    v3 = lambda t: t.view(T, t.shape[2], D)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        plan = fx.Plan(ctx, cu, Hq, Hkv, D, True)
+        if not args.attention_only:
+            fx.flexsp_pack(ctx, xq, sq, P, stream)
+            fx.flexsp_pack(ctx, xk, sk, P, stream)
+            fx.flexsp_pack(ctx, xv, sv, P, stream)
+        fx.flexsp_attn_varlen_fwd(ctx, plan, v3(sq), v3(sk), v3(sv), cud, v3(so), lse, stream=stream)
+        if not args.attention_only:
+            fx.flexsp_unpack(ctx, so, yo, stream)
+            fx.flexsp_pack(ctx, xg, sg, P, stream)
+        fx.flexsp_attn_varlen_bwd(ctx, plan, v3(sq), v3(sk), v3(sv), v3(so), v3(sg), lse, cud,
+                                  v3(sdq), v3(sdk), v3(sdv), stream=stream)
+        if not args.attention_only:
+            fx.flexsp_unpack(ctx, sdq, ydq, stream)
+            fx.flexsp_unpack(ctx, sdk, ydk, stream)
+            fx.flexsp_unpack(ctx, sdv, ydv, stream)
+        return plan
+
+    if args.attention_only:      # the slabs must hold data even when the permutes are skipped
+        for x, s in ((xq, sq), (xk, sk), (xv, sv), (xg, sg)):
+            fx.flexsp_pack(ctx, x, s, P, stream)
+
+    plans = []
+    for _ in range(args.warmup):
+        plans.append(step())
+    torch.cuda.synchronize()
+    for p in plans:
+        p.close()
+    plans = []
+
+    ctx.profile_start(16 * max(args.steps, 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plans.append(step())      # plans are released after the timed region (hipFree synchronises)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ctx.profile_stop()
+    for p in plans:
+        p.close()
+
+    ms_step = (t1 - t0) * 1e3 / max(args.steps, 1)
+    tflops = (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12
+
+    kern = {}
+    for name in fx.KERNELS:
+        ms, n = prof[name]
+        if n:
+            kern[name] = {"avg_ms": ms / n, "launches_per_step": n / max(args.steps, 1)}
+    # algorithmic FLOPs per launch, per (query, key) pair and head: fwd 2 GEMMs, dK/dV kernel 4 GEMMs
+    # (S, dP, dV, dK), dQ kernel 1 GEMM (its S and dP are recomputation, counted as zero)
+    alg = {"fwd": 4 * D * pairs_heads, "bwd_dkv": 8 * D * pairs_heads, "bwd_dq": 2 * D * pairs_heads}
+    dom = max((k for k in alg if k in kern), key=lambda k: kern[k]["avg_ms"] * kern[k]["launches_per_step"])
+    ach = alg[dom] / (kern[dom]["avg_ms"] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK / 1e12,
+                "unit": "TFLOP/s", "frac": ach / (BF16_MFMA_PEAK / 1e12), "traffic": None,
+                "avg_ms": kern[dom]["avg_ms"]}
+    attn_ms = sum(kern[k]["avg_ms"] * kern[k]["launches_per_step"] for k in ("fwd", "bwd_delta", "bwd_dkv", "bwd_dq") if k in kern)
+    out = {
+        "metric": "varlen causal attn fwd+bwd TFLOP/s (1 GPU) and % of bf16 MFMA peak",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "tokens": T, "sequences": len(lens), "max_len": max(lens),
+                   "hq": Hq, "hkv": Hkv, "head_dim": D, "causal": True, "sp_degree": P,
+                   "step": "plan+fwd+bwd" if args.attention_only else "plan+4 pack+fwd+bwd+4 unpack",
+                   "flops_fwd_bwd": f_fwd + f_bwd, "seed": cfg.seed},
+        "frac_of_bf16_mfma_peak": tflops * 1e12 / BF16_MFMA_PEAK,
+        "attention_kernels_only": {"ms": attn_ms, "tflops": (f_fwd + f_bwd) / (attn_ms * 1e-3) / 1e12,
+                                   "frac_of_bf16_mfma_peak": (f_fwd + f_bwd) / (attn_ms * 1e-3) / BF16_MFMA_PEAK},
+        "kernels": kern,
+        "roofline": roofline,
+    }
+
+    # ---- permute leg: achieved HBM bandwidth on the [32768, 32, 128] bf16, P = 8 shape, rotating
+    # over 4 distinct buffer pairs (2 GiB) so the 256 MB last-level cache cannot serve the reads
+    if not args.no_permute_leg:
+        c1 = wl.CONFIGS[1]
+        Tp, Hp_tot, Pp = c1.tokens, c1.hq * c1.sp_degree, c1.sp_degree
+        nbuf = 4
+        srcs = [torch.randn((Tp, Hp_tot, c1.d), device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(nbuf)]
+        dsts = [torch.empty((Pp, Tp, Hp_tot // Pp, c1.d), dtype=torch.bfloat16, device=dev) for _ in range(nbuf)]
+        res = {}
+        for which in ("pack", "unpack"):
+            def run(i):
+                if which == "pack":
+                    fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf], Pp, stream)
+                else:
+                    fx.flexsp_unpack(ctx, dsts[i % nbuf], srcs[i % nbuf], stream)
+            for i in range(10):
+                run(i)
+            ctx.profile_start(64)
+            for i in range(40):
+                run(i)
+            pr = ctx.profile_stop()
+            ms, n = pr[which]
+            nbytes = 2 * Tp * Hp_tot * c1.d * 2
+            res[which] = {"avg_ms": ms / n, "GBps": nbytes / (ms / n * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": nbytes / (ms / n * 1e-3) / HBM_PEAK}
+        out["permute"] = {"shape": [Tp, Hp_tot, c1.d], "sp_degree": Pp, "dtype": "bf16",
+                          "bytes_per_call": 2 * Tp * Hp_tot * c1.d * 2, "buffers_rotated": nbuf,
+                          "peak_GBps": HBM_PEAK / 1e9, **res}
+        del srcs, dsts
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        import oracle
+        budget = 2.5e11          # FLOPs: roughly 10-30 s of plain fp64 loops on 8-16 cores
+        per_task_cap = 8e9       # one (sequence, head) task runs on one thread
+        chosen, used = [], 0.0
+        for b in np.argsort(lens)[::-1]:
+            s = lens[int(b)]
+            per_head = 14 * D * s * (s + 1) // 2
+            if per_head * (Hq // Hkv) > per_task_cap or used + per_head * Hq > budget:
+                continue
+            chosen.append(int(b))
+            used += per_head * Hq
+        chosen.sort()
+        idx = np.concatenate([np.arange(cu[b], cu[b + 1]) for b in chosen])
+        sub_lens = [lens[b] for b in chosen]
+        # the same seeded distribution; the oracle gets its own [T, H, D] tensors of the sample's size
+        q_, k_, v_, g_ = wl.make_qkvdo(cfg, tokens=len(idx))
+        tc0 = time.perf_counter()
+        oracle.attn_fwd_bwd(q_, k_, v_, g_, wl.cu_seqlens(sub_lens), True)
+        tc1 = time.perf_counter()
+        fs = sum(wl.attn_flops(sub_lens, Hq, D, True))
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        out["cpu_baseline"] = {"value": fs / (tc1 - tc0) / 1e12, "unit": "TFLOP/s", "cores": threads,
+                               "kind": "oracle", "seconds": tc1 - tc0,
+                               "sample": f"{len(chosen)} of {len(lens)} sequences of the workload "
+                                         f"({len(idx)} tokens, longest {max(sub_lens)}), all {Hq} heads, fwd+bwd"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

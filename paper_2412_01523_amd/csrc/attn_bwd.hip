@@ -13,6 +13,8 @@
 // in a following MFMA.  Hence dK/dV computes S = Q K^T (rows = queries) and dQ computes
 // S^T = K Q^T (rows = keys).  Operands whose contraction index runs along the rows of a
 // row-major LDS tile are fetched with the LDS transpose read.
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace flexsp {
@@ -40,36 +42,38 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const AttnArgs a)
             acc += bf16_lo(x[i]) * bf16_lo(y[i]) + bf16_hi(x[i]) * bf16_hi(y[i]);
 #pragma unroll
         for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-        if (ok && sub == 0) a.delta_out[(int64_t)h * a.T + t] = acc;
+        if (ok && sub == 0) {
+            a.delta_out[(int64_t)h * a.T + t] = acc;
+            // the log-sum-exp in base 2, so the recomputation is one fma + exp2 per score
+            a.lse_out[(int64_t)h * a.T + t] = a.lse_in[(int64_t)h * a.T + t] * 1.4426950408889634f;
+        }
     }
 }
 
 // ------------------------------------------------------------------------------ dK / dV
-template <int D>
-struct DkvCfg {
-    static constexpr int KS = D / 16;
-    static constexpr int DB = D / 32;
-    static constexpr int STRIDE = D + 8;   // Q / dO tile row stride (elements)
-    static constexpr int CH = D / 8;
-    static constexpr int BQ = kDkvBq;      // query rows staged per step
-    static constexpr int NLD = BQ * CH / kThreads;
-};
-
+// One wavefront per SIMD (the accumulators for 32 keys x D of dK and dV, plus the K and V
+// fragments, need more than half the register file), so the overlap of matrix and vector work
+// has to come from inside the wavefront: a step handles two independent 32-query blocks, and the
+// exponentials of one block sit between the matrix instructions of the other.
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkv_kernel(const AttnArgs a)
 {
-    typedef DkvCfg<D> C;
-    __shared__ __attribute__((aligned(16))) uint16_t sQ[C::BQ * C::STRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t sG[C::BQ * C::STRIDE];
-    __shared__ __attribute__((aligned(16))) float sLse[C::BQ];
-    __shared__ __attribute__((aligned(16))) float sDel[C::BQ];
+    typedef LdsTile<D> L;
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int BQ = kDkvBq;                  // query rows per step: two 32-row blocks
+    constexpr int QTILE = BQ * L::ROWB;
+    constexpr int STEP = 2 * QTILE + 512;       // Q | dO | lse2[64] delta[64]
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STEP];
     __shared__ int s_item;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, hl = lane >> 5;
+    LaneOffsets<D> lo;
+    lo.init(lane);
     int cursor = 0;
-    const float log2e = 1.4426950408889634f;
 
     for (;;) {
         if (tid == 0) s_item = queue_fetch(a.pq, cursor);
@@ -83,14 +87,32 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkv_kernel(const AttnArg
         const int kvrow = kv0 + wave * 32 + r;  // this lane's key (column of S)
         const int wk_lo = kv0 + wave * 32;
 
+        const int qfirst = a.causal ? kv0 : 0;  // kv0 is a multiple of BQ
+        const int nsteps = (s - qfirst + BQ - 1) / BQ;
+        const int total = nsteps * a.G;
+
+        auto prefetch = [&](int step, int buf) {
+            const int h = g * a.G + step / nsteps;
+            const int qs = qfirst + (step % nsteps) * BQ;
+            char *base = smem + buf * STEP;
+            load_tile_async<D, BQ>(base, a.q + tok0 * a.q_st + (int64_t)h * a.q_sh, a.q_st, qs, s - 1, wave, lane);
+            load_tile_async<D, BQ>(base + QTILE, a.dO + tok0 * a.do_st + (int64_t)h * a.do_sh, a.do_st, qs, s - 1,
+                                   wave, lane);
+            if (wave < 2) {  // wavefront 0: lse2 of the 64 rows, wavefront 1: delta
+                const float *src = (wave ? a.delta_in : a.lse_in) + (int64_t)h * a.T + tok0 + min(qs + lane, s - 1);
+                global_to_lds4(src, base + 2 * QTILE + wave * 256);
+            }
+        };
+        if (total > 0) prefetch(0, 0);
+
         // K and V fragments of this wavefront's 32 keys (B operands: column = key, k = head dim)
-        bf16x8 kf[C::KS], vf[C::KS];
+        bf16x8 kf[KS], vf[KS];
         {
             const bool ok = kvrow < s;
             const uint16_t *kp = a.k + (tok0 + (ok ? kvrow : 0)) * a.k_st + (int64_t)g * a.k_sh + 8 * hl;
             const uint16_t *vp = a.v + (tok0 + (ok ? kvrow : 0)) * a.v_st + (int64_t)g * a.v_sh + 8 * hl;
 #pragma unroll
-            for (int ks = 0; ks < C::KS; ks++) {
+            for (int ks = 0; ks < KS; ks++) {
                 Frag8 f;
                 f.u = ok ? *(const u32x4 *)(kp + 16 * ks) : u32x4{0, 0, 0, 0};
                 kf[ks] = f.v;
@@ -98,119 +120,101 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkv_kernel(const AttnArg
                 vf[ks] = f.v;
             }
         }
-        f32x16 dkT[C::DB], dvT[C::DB];  // rows = head dim, column = key
+        f32x16 dkT[DB], dvT[DB];  // rows = head dim, column = key
 #pragma unroll
-        for (int db = 0; db < C::DB; db++)
+        for (int db = 0; db < DB; db++)
 #pragma unroll
             for (int i = 0; i < 16; i++) dkT[db][i] = dvT[db][i] = 0.f;
 
-        const int qfirst = a.causal ? kv0 : 0;  // kv0 is a multiple of BQ
-        const int nsteps = (s - qfirst + C::BQ - 1) / C::BQ;
-        const int total = nsteps * a.G;
-
-        u32x4 qreg[C::NLD], greg[C::NLD];
-        float lreg = 0.f, dreg = 0.f;
-        auto gload = [&](int step) {
-            const int h = g * a.G + step / nsteps;
-            const int qs = qfirst + (step % nsteps) * C::BQ;
-            const uint16_t *qb = a.q + tok0 * a.q_st + (int64_t)h * a.q_sh;
-            const uint16_t *gb = a.dO + tok0 * a.do_st + (int64_t)h * a.do_sh;
-#pragma unroll
-            for (int n = 0; n < C::NLD; n++) {
-                int c = n * kThreads + tid;
-                int row = c / C::CH, col = (c % C::CH) * 8;
-                bool ok = qs + row < s;
-                qreg[n] = ok ? *(const u32x4 *)(qb + (int64_t)(qs + row) * a.q_st + col) : u32x4{0, 0, 0, 0};
-                greg[n] = ok ? *(const u32x4 *)(gb + (int64_t)(qs + row) * a.do_st + col) : u32x4{0, 0, 0, 0};
-            }
-            if (tid < C::BQ) {
-                bool ok = qs + tid < s;
-                // +inf log-sum-exp makes P = 0 for rows past the end of the sequence
-                lreg = ok ? a.lse_in[(int64_t)h * a.T + tok0 + qs + tid] * log2e : INFINITY;
-                dreg = ok ? a.delta_in[(int64_t)h * a.T + tok0 + qs + tid] : 0.f;
-            }
-        };
-        auto lstore = [&]() {
-#pragma unroll
-            for (int n = 0; n < C::NLD; n++) {
-                int c = n * kThreads + tid;
-                int row = c / C::CH, col = (c % C::CH) * 8;
-                *(u32x4 *)(sQ + row * C::STRIDE + col) = qreg[n];
-                *(u32x4 *)(sG + row * C::STRIDE + col) = greg[n];
-            }
-            if (tid < C::BQ) {
-                sLse[tid] = lreg;
-                sDel[tid] = dreg;
-            }
-        };
-
-        if (total > 0) gload(0);
-        for (int step = 0; step < total; step++) {
-            const int qs = qfirst + (step % nsteps) * C::BQ;
+        auto step_fn = [&](auto bufc, int step) {
+            constexpr int BUF = decltype(bufc)::value;
+            const char *sQ = smem + BUF * STEP;
+            const char *sG = sQ + QTILE;
+            const float *sL = (const float *)(sQ + 2 * QTILE);  // lse2[64], delta[64]
+            const int q_lo = qfirst + (step % nsteps) * BQ;
+            wait_vmem();
             __syncthreads();
-            lstore();
-            __syncthreads();
-            if (step + 1 < total) gload(step + 1);
-#pragma unroll
-            for (int qb = 0; qb < C::BQ / 32; qb++) {
-                const int q_lo = qs + qb * 32;  // first query row of this block
-                if (q_lo >= s) continue;
-                if (a.causal && q_lo + 31 < wk_lo) continue;  // all rows before all keys
-                f32x16 sacc, pacc;
+            if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
+
+            // S = Q K^T and dP = dO V^T for one 32-query block (rows = queries, column = key)
+            auto scores = [&](int qb, f32x16 &sacc, f32x16 &pacc) {
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < C::KS; ks++) {
-                    bf16x8 qa = lds_frag(sQ, C::STRIDE, qb * 32, ks * 16, lane);
-                    sacc = mfma32(qa, kf[ks], sacc);
-                    bf16x8 ga = lds_frag(sG, C::STRIDE, qb * 32, ks * 16, lane);
-                    pacc = mfma32(ga, vf[ks], pacc);
+                for (int ks = 0; ks < KS; ks++) {
+                    sacc = mfma32(lds_nat(sQ, qb * 32 * L::ROWB + lo.nat[ks]), kf[ks], sacc);
+                    pacc = mfma32(lds_nat(sG, qb * 32 * L::ROWB + lo.nat[ks]), vf[ks], pacc);
                 }
-                // rows of the accumulator: query q_lo + 8*(i/4) + 4*hl + i%4
-                f32x4 l4[4], d4[4];
+            };
+            // P = exp2(S c - lse2), dS = P (dP - delta), both rounded to bf16 operand fragments.
+            // Accumulator register 4*i4 + e is query row q_lo + 32*qb + 8*i4 + 4*hl + e.
+            auto probs = [&](int qb, const f32x16 &sacc, const f32x16 &pacc, bool masked, uint32_t (&pp)[8],
+                             uint32_t (&dd)[8]) {
 #pragma unroll
                 for (int i4 = 0; i4 < 4; i4++) {
-                    l4[i4] = *(const f32x4 *)(sLse + qb * 32 + 8 * i4 + 4 * hl);
-                    d4[i4] = *(const f32x4 *)(sDel + qb * 32 + 8 * i4 + 4 * hl);
-                }
-                const bool need_mask = a.causal && (q_lo < wk_lo + 31);
-                uint32_t pp[8], dd[8];
+                    const f32x4 l4 = *(const f32x4 *)(sL + qb * 32 + 8 * i4 + 4 * hl);
+                    const f32x4 d4 = *(const f32x4 *)(sL + 64 + qb * 32 + 8 * i4 + 4 * hl);
+                    float p[4], ds[4];
 #pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], a.scale_l2, -l4[i >> 2][i & 3]));
-                    float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i + 1], a.scale_l2, -l4[i >> 2][(i + 1) & 3]));
-                    if (need_mask) {
-                        int qr = q_lo + 8 * (i >> 2) + 4 * hl + (i & 3);
-                        if (qr < kvrow) p0 = 0.f;
-                        if (qr + 1 < kvrow) p1 = 0.f;
+                    for (int e = 0; e < 4; e++) {
+                        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * i4 + e], a.scale_l2, -l4[e]));
+                        if (masked) {
+                            const int qr = q_lo + qb * 32 + 8 * i4 + 4 * hl + e;
+                            if ((a.causal && qr < kvrow) || qr >= s) p[e] = 0.f;
+                        }
+                        ds[e] = p[e] * (pacc[4 * i4 + e] - d4[e]);
                     }
-                    float s0 = p0 * (pacc[i] - d4[i >> 2][i & 3]);
-                    float s1 = p1 * (pacc[i + 1] - d4[i >> 2][(i + 1) & 3]);
-                    pp[i >> 1] = pack_bf16x2(p0, p1);
-                    dd[i >> 1] = pack_bf16x2(s0, s1);
+                    pp[2 * i4] = pack_bf16x2(p[0], p[1]);
+                    pp[2 * i4 + 1] = pack_bf16x2(p[2], p[3]);
+                    dd[2 * i4] = pack_bf16x2(ds[0], ds[1]);
+                    dd[2 * i4 + 1] = pack_bf16x2(ds[2], ds[3]);
                 }
+            };
+            // dV^T += dO^T P and dK^T += Q^T dS for one block
+            auto accumulate = [&](int qb, const uint32_t (&pp)[8], const uint32_t (&dd)[8]) {
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++) {
                     Frag8 pf, df;
                     pf.u = u32x4{pp[4 * hf], pp[4 * hf + 1], pp[4 * hf + 2], pp[4 * hf + 3]};
                     df.u = u32x4{dd[4 * hf], dd[4 * hf + 1], dd[4 * hf + 2], dd[4 * hf + 3]};
+                    const int rowoff = (qb * 32 + hf * 16) * L::ROWB;
 #pragma unroll
-                    for (int db = 0; db < C::DB; db++) {
-                        bf16x8 gt = lds_frag_tr(sG, C::STRIDE, qb * 32 + hf * 16, db * 32, lane);
-                        dvT[db] = mfma32(gt, pf.v, dvT[db]);
-                        bf16x8 qt = lds_frag_tr(sQ, C::STRIDE, qb * 32 + hf * 16, db * 32, lane);
-                        dkT[db] = mfma32(qt, df.v, dkT[db]);
+                    for (int db = 0; db < DB; db++) {
+                        dvT[db] = mfma32(lds_tr(sG, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), pf.v, dvT[db]);
+                        dkT[db] = mfma32(lds_tr(sQ, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), df.v, dkT[db]);
                     }
                 }
+            };
+
+            const bool plain = (!a.causal || q_lo >= wk_lo + 31) && q_lo + BQ <= s;
+#pragma unroll
+            for (int qb = 0; qb < 2; qb++) {
+                const int qb_lo = q_lo + qb * 32;
+                if (!plain) {
+                    if (qb_lo >= s) continue;
+                    if (a.causal && qb_lo + 31 < wk_lo) continue;  // all rows before all keys
+                }
+                f32x16 s0, p0;
+                uint32_t pp0[8], dd0[8];
+                scores(qb, s0, p0);
+                if (plain)
+                    probs(qb, s0, p0, false, pp0, dd0);
+                else
+                    probs(qb, s0, p0, true, pp0, dd0);
+                accumulate(qb, pp0, dd0);
             }
+        };
+        for (int step = 0; step < total; step += 2) {
+            step_fn(std::integral_constant<int, 0>{}, step);
+            if (step + 1 < total) step_fn(std::integral_constant<int, 1>{}, step + 1);
         }
 
         if (kvrow < s) {
             const int64_t eb = a.grad_f32 ? 4 : 2;
-            store_rowT<C::DB>((char *)a.dk + ((tok0 + kvrow) * a.dk_st + (int64_t)g * a.dk_sh) * eb, a.grad_f32,
-                              dkT, a.scale, hl);
-            store_rowT<C::DB>((char *)a.dv + ((tok0 + kvrow) * a.dv_st + (int64_t)g * a.dv_sh) * eb, a.grad_f32,
-                              dvT, 1.0f, hl);
+            store_rowT<DB>((char *)a.dk + ((tok0 + kvrow) * a.dk_st + (int64_t)g * a.dk_sh) * eb, a.grad_f32,
+                           dkT, a.scale, hl);
+            store_rowT<DB>((char *)a.dv + ((tok0 + kvrow) * a.dv_st + (int64_t)g * a.dv_sh) * eb, a.grad_f32,
+                           dvT, 1.0f, hl);
         }
         __syncthreads();
     }
@@ -219,28 +223,22 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkv_kernel(const AttnArg
 
 // ------------------------------------------------------------------------------ dQ
 template <int D>
-struct DqCfg {
-    static constexpr int KS = D / 16;
-    static constexpr int DB = D / 32;
-    static constexpr int KSTRIDE = D + 8;   // K tile: natural AND transpose reads
-    static constexpr int VSTRIDE = D + 8;   // V tile: natural reads
-    static constexpr int CH = D / 8;
-    static constexpr int NLD = kDqBk * CH / kThreads;
-};
-
-template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs a)
 {
-    typedef DqCfg<D> C;
-    __shared__ __attribute__((aligned(16))) uint16_t sK[kDqBk * C::KSTRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t sV[kDqBk * C::VSTRIDE];
+    typedef LdsTile<D> L;
+    constexpr int KS = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int TILE = kDqBk * L::ROWB;
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TILE];  // [buffer][K | V]
     __shared__ int s_item;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, hl = lane >> 5;
+    LaneOffsets<D> lo;
+    lo.init(lane);
     int cursor = 0;
-    const float log2e = 1.4426950408889634f;
 
     for (;;) {
         if (tid == 0) s_item = queue_fetch(a.pq, cursor);
@@ -253,16 +251,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         const int64_t tok0 = it.seq_start;
         const int kv_end = a.causal ? min(s, q0 + kDqBq) : s;
         const int ntiles = (kv_end + kDqBk - 1) / kDqBk;
+        const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
+        const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
+        auto prefetch = [&](int t, int buf) {
+            load_tile_async<D, kDqBk>(smem + buf * 2 * TILE, kbase, a.k_st, t * kDqBk, s - 1, wave, lane);
+            load_tile_async<D, kDqBk>(smem + buf * 2 * TILE + TILE, vbase, a.v_st, t * kDqBk, s - 1, wave, lane);
+        };
+        prefetch(0, 0);
+
         const int qrow = q0 + wave * 32 + r;
         const int wq_lo = q0 + wave * 32;
         const bool qok = qrow < s;
-
-        bf16x8 qf[C::KS], gf[C::KS];  // B operands: column = query row, k = head dim
+        bf16x8 qf[KS], gf[KS];  // B operands: column = query row, k = head dim
         {
             const uint16_t *qp = a.q + (tok0 + (qok ? qrow : 0)) * a.q_st + (int64_t)h * a.q_sh + 8 * hl;
             const uint16_t *gp = a.dO + (tok0 + (qok ? qrow : 0)) * a.do_st + (int64_t)h * a.do_sh + 8 * hl;
 #pragma unroll
-            for (int ks = 0; ks < C::KS; ks++) {
+            for (int ks = 0; ks < KS; ks++) {
                 Frag8 f;
                 f.u = qok ? *(const u32x4 *)(qp + 16 * ks) : u32x4{0, 0, 0, 0};
                 qf[ks] = f.v;
@@ -270,46 +275,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                 gf[ks] = f.v;
             }
         }
-        const float lse2 = qok ? a.lse_in[(int64_t)h * a.T + tok0 + qrow] * log2e : INFINITY;
+        // +inf log-sum-exp makes P = 0 for rows past the end of the sequence
+        const float lse2 = qok ? a.lse_in[(int64_t)h * a.T + tok0 + qrow] : INFINITY;
         const float delta = qok ? a.delta_in[(int64_t)h * a.T + tok0 + qrow] : 0.f;
 
-        f32x16 dqT[C::DB];  // rows = head dim, column = query
+        f32x16 dqT[DB];  // rows = head dim, column = query
 #pragma unroll
-        for (int db = 0; db < C::DB; db++)
+        for (int db = 0; db < DB; db++)
 #pragma unroll
             for (int i = 0; i < 16; i++) dqT[db][i] = 0.f;
 
-        const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
-        const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
-        u32x4 kreg[C::NLD], vreg[C::NLD];
-        auto gload = [&](int kv0) {
-#pragma unroll
-            for (int n = 0; n < C::NLD; n++) {
-                int c = n * kThreads + tid;
-                int row = c / C::CH, col = (c % C::CH) * 8;
-                bool ok = kv0 + row < s;
-                kreg[n] = ok ? *(const u32x4 *)(kbase + (int64_t)(kv0 + row) * a.k_st + col) : u32x4{0, 0, 0, 0};
-                vreg[n] = ok ? *(const u32x4 *)(vbase + (int64_t)(kv0 + row) * a.v_st + col) : u32x4{0, 0, 0, 0};
-            }
-        };
-        auto lstore = [&]() {
-#pragma unroll
-            for (int n = 0; n < C::NLD; n++) {
-                int c = n * kThreads + tid;
-                int row = c / C::CH, col = (c % C::CH) * 8;
-                *(u32x4 *)(sK + row * C::KSTRIDE + col) = kreg[n];
-                *(u32x4 *)(sV + row * C::VSTRIDE + col) = vreg[n];
-            }
-        };
-
-        gload(0);
-        for (int t = 0; t < ntiles; t++) {
+        auto step_fn = [&](auto bufc, int t) {
+            constexpr int BUF = decltype(bufc)::value;
+            const char *sK = smem + BUF * 2 * TILE;
+            const char *sV = sK + TILE;
             const int kv0 = t * kDqBk;
+            wait_vmem();
             __syncthreads();
-            lstore();
-            __syncthreads();
-            if (t + 1 < ntiles) gload(kv0 + kDqBk);
-            if (a.causal && kv0 > wq_lo + 31) continue;
+            if (t + 1 < ntiles) prefetch(t + 1, BUF ^ 1);
+            if (a.causal && kv0 > wq_lo + 31) return;
 
             f32x16 sacc[2], pacc[2];
 #pragma unroll
@@ -317,13 +301,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[kb][i] = pacc[kb][i] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < C::KS; ks++)
+            for (int ks = 0; ks < KS; ks++)
 #pragma unroll
                 for (int kb = 0; kb < 2; kb++) {
-                    bf16x8 ka = lds_frag(sK, C::KSTRIDE, kb * 32, ks * 16, lane);
-                    sacc[kb] = mfma32(ka, qf[ks], sacc[kb]);
-                    bf16x8 va = lds_frag(sV, C::VSTRIDE, kb * 32, ks * 16, lane);
-                    pacc[kb] = mfma32(va, gf[ks], pacc[kb]);
+                    sacc[kb] = mfma32(lds_nat(sK, kb * 32 * L::ROWB + lo.nat[ks]), qf[ks], sacc[kb]);
+                    pacc[kb] = mfma32(lds_nat(sV, kb * 32 * L::ROWB + lo.nat[ks]), gf[ks], pacc[kb]);
                 }
             const bool need_mask = a.causal ? (kv0 + kDqBk - 1 > wq_lo) : (kv0 + kDqBk > s);
             const int lim = a.causal ? qrow : s - 1;
@@ -348,18 +330,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                 for (int hf = 0; hf < 2; hf++) {
                     Frag8 df;
                     df.u = u32x4{dd[kb][4 * hf], dd[kb][4 * hf + 1], dd[kb][4 * hf + 2], dd[kb][4 * hf + 3]};
+                    const int rowoff = (kb * 32 + hf * 16) * L::ROWB;
 #pragma unroll
-                    for (int db = 0; db < C::DB; db++) {
-                        bf16x8 kt = lds_frag_tr(sK, C::KSTRIDE, kb * 32 + hf * 16, db * 32, lane);
-                        dqT[db] = mfma32(kt, df.v, dqT[db]);
-                    }
+                    for (int db = 0; db < DB; db++)
+                        dqT[db] = mfma32(lds_tr(sK, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), df.v, dqT[db]);
                 }
+        };
+        for (int t = 0; t < ntiles; t += 2) {
+            step_fn(std::integral_constant<int, 0>{}, t);
+            if (t + 1 < ntiles) step_fn(std::integral_constant<int, 1>{}, t + 1);
         }
 
         if (qok) {
             const int64_t eb = a.grad_f32 ? 4 : 2;
-            store_rowT<C::DB>((char *)a.dq + ((tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh) * eb, a.grad_f32,
-                              dqT, a.scale, hl);
+            store_rowT<DB>((char *)a.dq + ((tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh) * eb, a.grad_f32,
+                           dqT, a.scale, hl);
         }
         __syncthreads();
     }

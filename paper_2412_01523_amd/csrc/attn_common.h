@@ -51,30 +51,128 @@ __device__ __forceinline__ s16x4 lds_read_tr(const uint16_t *p)
         (__attribute__((address_space(3))) s16x4 *)(uintptr_t)p);
 }
 
-// Operand fragment (A or B of mfma32) whose k index runs over the ROWS of a row-major LDS
-// tile and whose free index (32 wide) runs over its columns: for lane l the fragment holds
-// tile[row0 + kmap(j)][col0 + l % 32], j = 0..7, with kmap(j) = 4*hl + j for j < 4 and
-// 8 + 4*hl + (j - 4) for j >= 4 -- the order in which a 32x32 accumulator keeps its rows,
-// so an accumulator block can be the other operand without any shuffle.
-__device__ __forceinline__ bf16x8 lds_frag_tr(const uint16_t *tile, int stride, int row0, int col0, int lane)
+// ------------------------------------------------------------------------------------------
+// LDS tiles.  A tile holds rows of D bf16 (D*2 bytes, no padding) as 16-byte chunks; the chunk
+// index is XOR-swizzled with a function of the row so that both access patterns below touch
+// every bank once:
+//   natural read  (ds_read_b128): 16 lanes read the same chunk of 16 consecutive rows;
+//   transpose read (ds_read_b64_tr_b16): 32 lanes read 4 consecutive chunks of 4 consecutive rows.
+// For D = 128 (16 chunks per row) the swizzle swaps the two 2-bit fields of row % 16; for D = 64
+// (8 chunks, two rows per 256 bytes) it uses row bits 1..3.
+template <int D>
+struct LdsTile {
+    static constexpr int CH = D / 8;    // 16-byte chunks per row
+    static constexpr int ROWB = D * 2;  // bytes per row
+    __device__ static __forceinline__ int sw(int row)
+    {
+        return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    }
+};
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
+
+// 16 bytes per lane straight from global memory into LDS: lane l's data lands at lds + 16*l.
+// `lds` must be wave-uniform.  Completion is tracked by vmcnt.
+__device__ __forceinline__ void global_to_lds16(const void *g, void *lds)
 {
-    int i = lane & 15, gg = lane >> 4;
-    int hl = gg >> 1;
-    const uint16_t *p = tile + (row0 + 4 * hl + (i >> 2)) * stride + col0 + 16 * (gg & 1) + 4 * (i & 3);
+    __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds, 16, 0, 0);
+}
+__device__ __forceinline__ void global_to_lds4(const void *g, void *lds)
+{
+    __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds, 4, 0, 0);
+}
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0)
+
+// Copies ROWS rows of a row-major global matrix (row r at g + r*stride elements, D bf16 each)
+// into a swizzled LDS tile, asynchronously, with all 256 threads.  Row `first + r` is clamped to
+// `last_valid`, so rows past the end of a sequence duplicate its last row (finite data; callers
+// mask them).
+template <int D, int ROWS>
+__device__ __forceinline__ void load_tile_async(char *tile, const uint16_t *g, int64_t stride, int first,
+                                                int last_valid, int wave, int lane)
+{
+    typedef LdsTile<D> L;
+    constexpr int N = ROWS * L::CH / kThreads;
+    static_assert(N >= 1 && ROWS * L::CH % kThreads == 0, "tile must split evenly over the workgroup");
+#pragma unroll
+    for (int n = 0; n < N; n++) {
+        const int pos = n * kThreads + wave * 64 + lane;
+        const int row = pos / L::CH;
+        const int c = (pos % L::CH) ^ L::sw(row);
+        const int grow = min(first + row, last_valid);
+        global_to_lds16(g + (int64_t)grow * stride + c * 8, tile + (n * kThreads + wave * 64) * 16);
+    }
+}
+
+// Per-lane byte offsets of operand fragments inside a tile (computed once per kernel).
+//   nat[ks]: fragment whose k index runs along the columns: rows rb*32 + l%32 (add rb*32*ROWB),
+//            columns 16*ks + 8*hl .. +7.
+//   tr[db][h]: fragment whose k index runs over ROWS (transpose read) and whose free index is
+//            columns db*32 + l%32: lane's first (h=0) / second (h=1) 4-row read; for k slot j the
+//            row is R0 + kmap(j), kmap(j) = 4*hl + j (j<4), 8 + 4*hl + (j-4) (j>=4): the order in
+//            which a 32x32 accumulator keeps its rows, so an accumulator block can be the other
+//            operand without a shuffle.  Add R0*ROWB with R0 a multiple of 16.
+template <int D>
+struct LaneOffsets {
+    int nat[D / 16];
+    int tr[D / 32][2];
+    __device__ __forceinline__ void init(int lane)
+    {
+        typedef LdsTile<D> L;
+        const int r = lane & 31, hl = lane >> 5;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ks++) nat[ks] = r * L::ROWB + (((2 * ks + hl) ^ L::sw(r)) << 4);
+        const int i = lane & 15, gg = lane >> 4;
+        const int cl = 2 * (gg & 1) + ((i & 3) >> 1);
+#pragma unroll
+        for (int db = 0; db < D / 32; db++)
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const int row = 4 * hl + (i >> 2) + 8 * h;
+                tr[db][h] = row * L::ROWB + (((4 * db + cl) ^ L::sw(row)) << 4) + (i & 1) * 8;
+            }
+    }
+};
+
+__device__ __forceinline__ bf16x8 lds_nat(const char *tile, int off)
+{
     Frag8 f;
-    f.h[0] = lds_read_tr(p);
-    f.h[1] = lds_read_tr(p + 8 * stride);
+    f.u = *(const u32x4 *)(tile + off);
+    return f.v;
+}
+__device__ __forceinline__ bf16x8 lds_tr(const char *tile, int off0, int off1)
+{
+    Frag8 f;
+    f.h[0] = lds_read_tr((const uint16_t *)(tile + off0));
+    f.h[1] = lds_read_tr((const uint16_t *)(tile + off1));
     return f.v;
 }
 
-// Operand fragment whose k index runs along the columns of a row-major LDS tile (natural
-// read): tile[row0 + l % 32][col0 + 8*hl .. + 7].
-__device__ __forceinline__ bf16x8 lds_frag(const uint16_t *tile, int stride, int row0, int col0, int lane)
+// max / sum across the two half-waves: every lane gets op(x[l % 32], x[l % 32 + 32]).
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
+// second; fed the same value twice it returns {x[l % 32], x[l % 32 + 32]} in every lane.
+// (The two results are copied into scalars before the bit casts: casting the vector's elements
+// in place made the compiler read element 0 twice.)
+__device__ __forceinline__ void halves_both(float x, float &lo, float &hi)
 {
-    const uint16_t *p = tile + (row0 + (lane & 31)) * stride + col0 + 8 * (lane >> 5);
-    Frag8 f;
-    f.u = *(const u32x4 *)p;
-    return f.v;
+    const unsigned a = __builtin_bit_cast(unsigned, x);
+    auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    lo = __builtin_bit_cast(float, r0);
+    hi = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float halves_max(float x)
+{
+    float lo, hi;
+    halves_both(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float halves_sum(float x)
+{
+    float lo, hi;
+    halves_both(x, lo, hi);
+    return lo + hi;
 }
 
 // Epilogue store of a transposed accumulator (rows = head dim, column = this lane's token):

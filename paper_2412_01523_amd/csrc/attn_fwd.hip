@@ -3,38 +3,39 @@
 //
 // One work item = 128 query rows of one (sequence, head).  A workgroup of 4 wavefronts
 // takes items from the longest-first queues until they are empty.  Each wavefront owns 32
-// query rows and keeps their Q in registers.  Key/value tiles of 64 rows are staged in LDS.
+// query rows and keeps their Q in registers.  Key/value tiles of 64 rows go straight from
+// global memory into swizzled LDS tiles (no staging registers), double-buffered: the next
+// tile is in flight while this one is consumed, one barrier per tile.
 // The score block is computed TRANSPOSED, S^T = K Q^T, so that in the 32x32 accumulator a
 // lane holds one query (its column) and 16 keys: the row-wise softmax is a reduction over a
 // lane's own registers plus one exchange with the lane 32 away, and the exponentiated block,
 // rounded to bf16, is directly the B operand of O^T += V^T P^T.  V^T fragments come from
-// the row-major V tile through the LDS transpose read.
+// the row-major V tile through the LDS transpose read.  The running output is rescaled only
+// when some row's maximum actually grew.
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace flexsp {
 namespace {
 
 template <int D>
-struct FwdCfg {
-    static constexpr int KS = D / 16;         // k steps of the score product
-    static constexpr int DB = D / 32;         // 32-wide blocks of the head dim
-    static constexpr int KSTRIDE = D + 8;     // K tile row stride (elements): natural reads
-    static constexpr int VSTRIDE = D + 32;    // V tile row stride: transpose reads
-    static constexpr int CH = D / 8;          // 16-byte chunks per row
-    static constexpr int NLD = kFwdBk * CH / kThreads;  // chunks per thread per tile
-};
-
-template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
 {
-    typedef FwdCfg<D> C;
-    __shared__ __attribute__((aligned(16))) uint16_t sK[kFwdBk * C::KSTRIDE];
-    __shared__ __attribute__((aligned(16))) uint16_t sV[kFwdBk * C::VSTRIDE];
+    typedef LdsTile<D> L;
+    constexpr int KS = D / 16;                  // k steps of the score product
+    constexpr int DB = D / 32;                  // 32-wide blocks of the head dim
+    constexpr int TILE = kFwdBk * L::ROWB;      // bytes of one 64-row tile
+    // [buffer][K | V]
+    __shared__ __attribute__((aligned(1024))) char smem[4 * TILE];
     __shared__ int s_item;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, hl = lane >> 5;
+    LaneOffsets<D> lo;
+    lo.init(lane);
     int cursor = 0;
 
     for (;;) {
@@ -48,64 +49,47 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         const int64_t tok0 = it.seq_start;
         const int kv_end = a.causal ? min(s, q0 + kFwdBq) : s;  // keys this item needs
         const int ntiles = (kv_end + kFwdBk - 1) / kFwdBk;
+        const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
+        const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
+
+        auto prefetch = [&](int t, int buf) {
+            load_tile_async<D, kFwdBk>(smem + buf * 2 * TILE, kbase, a.k_st, t * kFwdBk, s - 1, wave, lane);
+            load_tile_async<D, kFwdBk>(smem + buf * 2 * TILE + TILE, vbase, a.v_st, t * kFwdBk, s - 1, wave, lane);
+        };
+        prefetch(0, 0);
 
         // ---- Q fragments (B operand: column = query row, k = head dim), kept in registers
         const int qrow = q0 + wave * 32 + r;  // row inside the sequence
-        bf16x8 qf[C::KS];
+        const int wq_lo = q0 + wave * 32;     // smallest query row of this wavefront
+        bf16x8 qf[KS];
         {
             const bool ok = qrow < s;
             const uint16_t *qp = a.q + (tok0 + (ok ? qrow : 0)) * a.q_st + (int64_t)h * a.q_sh + 8 * hl;
 #pragma unroll
-            for (int ks = 0; ks < C::KS; ks++) {
+            for (int ks = 0; ks < KS; ks++) {
                 Frag8 f;
                 f.u = ok ? *(const u32x4 *)(qp + 16 * ks) : u32x4{0, 0, 0, 0};
                 qf[ks] = f.v;
             }
         }
 
-        f32x16 oacc[C::DB];
+        f32x16 oacc[DB];
 #pragma unroll
-        for (int db = 0; db < C::DB; db++)
+        for (int db = 0; db < DB; db++)
 #pragma unroll
             for (int i = 0; i < 16; i++) oacc[db][i] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f;
+        float m_run = -INFINITY, l_run = 0.f, moff = 0.f;
 
-        const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
-        const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
-
-        // register staging of the next K/V tile
-        u32x4 kreg[C::NLD], vreg[C::NLD];
-        auto gload = [&](int kv0) {
-#pragma unroll
-            for (int n = 0; n < C::NLD; n++) {
-                int c = n * kThreads + tid;
-                int row = c / C::CH, col = (c % C::CH) * 8;
-                bool ok = kv0 + row < s;
-                kreg[n] = ok ? *(const u32x4 *)(kbase + (int64_t)(kv0 + row) * a.k_st + col) : u32x4{0, 0, 0, 0};
-                vreg[n] = ok ? *(const u32x4 *)(vbase + (int64_t)(kv0 + row) * a.v_st + col) : u32x4{0, 0, 0, 0};
-            }
-        };
-        auto lstore = [&]() {
-#pragma unroll
-            for (int n = 0; n < C::NLD; n++) {
-                int c = n * kThreads + tid;
-                int row = c / C::CH, col = (c % C::CH) * 8;
-                *(u32x4 *)(sK + row * C::KSTRIDE + col) = kreg[n];
-                *(u32x4 *)(sV + row * C::VSTRIDE + col) = vreg[n];
-            }
-        };
-
-        gload(0);
-        const int wq_lo = q0 + wave * 32;  // smallest query row of this wavefront
-        for (int t = 0; t < ntiles; t++) {
+        auto step = [&](auto bufc, int t) {
+            constexpr int BUF = decltype(bufc)::value;
+            const char *sK = smem + BUF * 2 * TILE;
+            const char *sV = sK + TILE;
             const int kv0 = t * kFwdBk;
-            __syncthreads();  // everyone is done reading the previous tile
-            lstore();
-            __syncthreads();
-            if (t + 1 < ntiles) gload(kv0 + kFwdBk);
-
+            wait_vmem();      // this wavefront's share of tile t has landed
+            __syncthreads();  // everybody's has, and everybody is done with tile t-1
+            if (t + 1 < ntiles) prefetch(t + 1, BUF ^ 1);
             // wavefronts whose rows all lie above this tile (causal) have nothing to do
-            if (a.causal && kv0 > wq_lo + 31) continue;
+            if (a.causal && kv0 > wq_lo + 31) return;
 
             // ---- S^T = K Q^T : two 32-key blocks
             f32x16 sacc[2];
@@ -114,13 +98,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[kb][i] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < C::KS; ks++) {
+            for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-                for (int kb = 0; kb < 2; kb++) {
-                    bf16x8 kf = lds_frag(sK, C::KSTRIDE, kb * 32, ks * 16, lane);
-                    sacc[kb] = mfma32(kf, qf[ks], sacc[kb]);
-                }
-            }
+                for (int kb = 0; kb < 2; kb++)
+                    sacc[kb] = mfma32(lds_nat(sK, kb * 32 * L::ROWB + lo.nat[ks]), qf[ks], sacc[kb]);
             // ---- mask (only tiles that touch the diagonal or the end of the sequence)
             const bool need_mask = a.causal ? (kv0 + kFwdBk - 1 > wq_lo) : (kv0 + kFwdBk > s);
             if (need_mask) {
@@ -134,16 +115,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                     }
             }
             // ---- online softmax (one query per lane, 32 of its keys here, 32 in lane^32)
-            float mx = sacc[0][0];
+            float mx = fmaxf(sacc[0][0], sacc[1][0]);
 #pragma unroll
-            for (int kb = 0; kb < 2; kb++)
+            for (int i = 1; i < 16; i++) mx = fmaxf(mx, fmaxf(sacc[0][i], sacc[1][i]));
+            mx = halves_max(mx);
+            if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {  // some row's maximum grew
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_l2);
+                m_run = m_new;
+                moff = m_new * a.scale_l2;
+                l_run *= alpha;
 #pragma unroll
-                for (int i = 0; i < 16; i++) mx = fmaxf(mx, sacc[kb][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * a.scale_l2);
-            const float moff = m_use * a.scale_l2;
+                for (int db = 0; db < DB; db++)
+#pragma unroll
+                    for (int i = 0; i < 16; i++) oacc[db][i] *= alpha;
+            }
             float psum = 0.f;
             uint32_t pk[2][8];
 #pragma unroll
@@ -155,12 +141,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                     psum += p0 + p1;
                     pk[kb][i >> 1] = pack_bf16x2(p0, p1);
                 }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
-#pragma unroll
-            for (int db = 0; db < C::DB; db++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) oacc[db][i] *= alpha;
+            l_run += psum;
             // ---- O^T += V^T P^T
 #pragma unroll
             for (int kb = 0; kb < 2; kb++)
@@ -168,31 +149,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                 for (int hf = 0; hf < 2; hf++) {
                     Frag8 pf;
                     pf.u = u32x4{pk[kb][4 * hf], pk[kb][4 * hf + 1], pk[kb][4 * hf + 2], pk[kb][4 * hf + 3]};
+                    const int rowoff = (kb * 32 + hf * 16) * L::ROWB;
 #pragma unroll
-                    for (int db = 0; db < C::DB; db++) {
-                        bf16x8 vf = lds_frag_tr(sV, C::VSTRIDE, kb * 32 + hf * 16, db * 32, lane);
-                        oacc[db] = mfma32(vf, pf.v, oacc[db]);
-                    }
+                    for (int db = 0; db < DB; db++)
+                        oacc[db] = mfma32(lds_tr(sV, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), pf.v, oacc[db]);
                 }
+        };
+
+        for (int t = 0; t < ntiles; t += 2) {
+            step(std::integral_constant<int, 0>{}, t);
+            if (t + 1 < ntiles) step(std::integral_constant<int, 1>{}, t + 1);
         }
 
         // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
-        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        const float l_tot = halves_sum(l_run);
         if (qrow < s) {
-            const float inv = 1.0f / l_tot;
-            uint16_t *op = a.out_o + (tok0 + qrow) * a.o_st + (int64_t)h * a.o_sh;
-#pragma unroll
-            for (int db = 0; db < C::DB; db++)
-#pragma unroll
-                for (int i4 = 0; i4 < 4; i4++) {
-                    u32x2 w;
-                    w[0] = pack_bf16x2(oacc[db][4 * i4] * inv, oacc[db][4 * i4 + 1] * inv);
-                    w[1] = pack_bf16x2(oacc[db][4 * i4 + 2] * inv, oacc[db][4 * i4 + 3] * inv);
-                    *(u32x2 *)(op + db * 32 + 8 * i4 + 4 * hl) = w;
-                }
+            store_rowT<DB>(a.out_o + (tok0 + qrow) * a.o_st + (int64_t)h * a.o_sh, false, oacc, 1.0f / l_tot, hl);
             if (hl == 0) a.lse_out[(int64_t)h * a.T + tok0 + qrow] = m_run * a.scale + __logf(l_tot);
         }
-        __syncthreads();  // s_item and the LDS tiles are reused by the next item
+        __syncthreads();  // s_item and the LDS buffers are reused by the next item
     }
     if (tid == 0) queue_retire(a.pq);
 }

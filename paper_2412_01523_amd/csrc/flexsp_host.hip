@@ -325,7 +325,7 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
     p->B = B; p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->causal = causal ? 1 : 0;
     p->T = cu[B];
     p->dev_base = nullptr; p->dev_bytes = 0; p->delta = nullptr;
-    p->delta_bytes = (size_t)p->T * Hq * sizeof(float);
+    p->delta_bytes = 2 * (size_t)p->T * Hq * sizeof(float);  // delta and log2-domain LSE, [Hq, T] each
     try {
         p->cu.assign(cu, cu + B + 1);
         int nq = ctx->num_xcd;
@@ -533,7 +533,9 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
     a.dq_st = dq.stride_token; a.dq_sh = dq.stride_head;
     a.dk_st = dk.stride_token; a.dk_sh = dk.stride_head;
     a.dv_st = dv.stride_token; a.dv_sh = dv.stride_head;
-    a.lse_in = lse;
+    float *lse2 = plan->delta + (size_t)plan->T * plan->Hq;
+    a.lse_in = lse;       // the preprocess kernel reads the caller's LSE ...
+    a.lse_out = lse2;     // ... and writes it in the log2 domain next to delta
     a.delta_out = plan->delta;
     a.delta_in = plan->delta;
     a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
@@ -545,6 +547,7 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
         e = launch_attn_bwd_delta(a, plan->D, s);
     }
     if (e != hipSuccess) return hip_fail(e);
+    a.lse_in = lse2;
     a.pq = plan->dq[FLEXSP_PASS_BWD_DKV];
     {
         Timed tm(ctx, FLEXSP_K_BWD_DKV, s);

@@ -94,7 +94,7 @@ def test_plan_covers_every_tile_once_longest_first(host_ctx, causal):
             for i in items[offs[x]:offs[x + 1]]:
                 key = (int(i["seq_start"]), int(i["head"]))
                 assert owner.setdefault(key, x) == x
-    assert plan.workspace_bytes == sum(lens) * hq * 4
+    assert plan.workspace_bytes == 2 * sum(lens) * hq * 4      # delta and log2-domain LSE
     plan.close()
 
 

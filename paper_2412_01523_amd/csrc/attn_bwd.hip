@@ -51,61 +51,86 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const AttnArgs a)
 }
 
 // ------------------------------------------------------------------------------ dK / dV
-// One wavefront per SIMD (the accumulators for 32 keys x D of dK and dV, plus the K and V
-// fragments, need more than half the register file), so the overlap of matrix and vector work
-// has to come from inside the wavefront: a step handles two independent 32-query blocks, and the
-// exponentials of one block sit between the matrix instructions of the other.
+// One work item = 64 keys of one (sequence, kv head).  The accumulators of 32 keys x D for both
+// dK and dV, next to the K and V fragments, would take more than half of the register file and
+// leave one wavefront per SIMD with nothing to overlap its exponentials with.  So TWO wavefronts
+// share each block of 32 keys: per step of 64 query rows, wavefront j of the pair computes
+// S = Q K^T, dP = dO V^T, P and dS for query block j only, the pair swaps the bf16 P / dS
+// fragments through LDS (a fragment is written and read back by the same lane numbers, so the
+// swap is a plain linear copy), and then each wavefront accumulates dV^T += dO^T P and
+// dK^T += Q^T dS for BOTH query blocks but only for its own half of the head dim.  No matrix
+// work is duplicated, every wavefront fits in 256 registers, and two workgroups share a CU.
 template <int D>
-__global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkv_kernel(const AttnArgs a)
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArgs a)
 {
     typedef LdsTile<D> L;
+    typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
     constexpr int KS = D / 16;
-    constexpr int DB = D / 32;
+    constexpr int DBH = D / 64;                 // 32-wide head-dim blocks per wavefront
     constexpr int BQ = kDkvBq;                  // query rows per step: two 32-row blocks
     constexpr int QTILE = BQ * L::ROWB;
-    constexpr int STEP = 2 * QTILE + 512;       // Q | dO | lse2[64] delta[64]
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STEP];
-    __shared__ int s_item;
+    constexpr int STEP = 2 * QTILE;             // Q | dO
+    constexpr int XSLOT = 4096;                 // P (2 KB) and dS (2 KB) of one 32 x 32 block
+    // [buffer][Q | dO] then 4 exchange slots; the first word of the exchange area doubles as the
+    // item broadcast slot between items
+    __shared__ __attribute__((aligned(1024))) char smem[2 * STEP + 4 * XSLOT];
+    char *const exch = smem + 2 * STEP;
+    volatile int *const s_item = (volatile int *)exch;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kb = wave >> 1, j = wave & 1;     // key block, role inside the pair
     const int r = lane & 31, hl = lane >> 5;
-    LaneOffsets<D> lo;
-    lo.init(lane);
+    int nat[KS];                                // natural-read offsets, as in LaneOffsets
+    int trw[DBH][2];                            // transpose-read offsets of this wavefront's head-dim blocks
+    {
+        LaneOffsets<D> lo;
+        lo.init(lane);
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) nat[ks] = lo.nat[ks];
+#pragma unroll
+        for (int d = 0; d < DBH; d++)
+#pragma unroll
+            for (int h = 0; h < 2; h++) trw[d][h] = j ? lo.tr[DBH + d][h] : lo.tr[d][h];
+    }
     int cursor = 0;
 
     for (;;) {
-        if (tid == 0) s_item = queue_fetch(a.pq, cursor);
+        __syncthreads();  // the exchange area is free again
+        if (tid == 0) *s_item = queue_fetch(a.pq, cursor);
         __syncthreads();
-        const int item = s_item;
+        const int item = __builtin_amdgcn_readfirstlane(*s_item);  // wave-uniform: everything derived from it stays scalar
         if (item < 0) break;
         const flexsp_item it = a.pq.items[item];
         const int s = it.seq_len, g = it.head;
         const int kv0 = it.tile * kDkvBk;
         const int64_t tok0 = it.seq_start;
-        const int kvrow = kv0 + wave * 32 + r;  // this lane's key (column of S)
-        const int wk_lo = kv0 + wave * 32;
+        const int wk_lo = kv0 + kb * 32;
+        const int kvrow = wk_lo + r;  // this lane's key (column of S)
 
         const int qfirst = a.causal ? kv0 : 0;  // kv0 is a multiple of BQ
         const int nsteps = (s - qfirst + BQ - 1) / BQ;
         const int total = nsteps * a.G;
 
+        const uint32_t goffq = tile_goff<D>(a.q_st, wave, lane), goffg = tile_goff<D>(a.do_st, wave, lane);
         auto prefetch = [&](int step, int buf) {
             const int h = g * a.G + step / nsteps;
             const int qs = qfirst + (step % nsteps) * BQ;
             char *base = smem + buf * STEP;
-            load_tile_async<D, BQ>(base, a.q + tok0 * a.q_st + (int64_t)h * a.q_sh, a.q_st, qs, s - 1, wave, lane);
-            load_tile_async<D, BQ>(base + QTILE, a.dO + tok0 * a.do_st + (int64_t)h * a.do_sh, a.do_st, qs, s - 1,
-                                   wave, lane);
-            if (wave < 2) {  // wavefront 0: lse2 of the 64 rows, wavefront 1: delta
-                const float *src = (wave ? a.delta_in : a.lse_in) + (int64_t)h * a.T + tok0 + min(qs + lane, s - 1);
-                global_to_lds4(src, base + 2 * QTILE + wave * 256);
+            const uint16_t *qb = a.q + tok0 * a.q_st + (int64_t)h * a.q_sh;
+            const uint16_t *gb = a.dO + tok0 * a.do_st + (int64_t)h * a.do_sh;
+            if (qs + BQ <= s) {  // whole tile inside the sequence
+                load_tile_async_fast<D, BQ>(base, qb + (int64_t)qs * a.q_st, a.q_st, goffq, wave);
+                load_tile_async_fast<D, BQ>(base + QTILE, gb + (int64_t)qs * a.do_st, a.do_st, goffg, wave);
+            } else {
+                load_tile_async<D, BQ>(base, qb, a.q_st, qs, s - 1, wave, lane);
+                load_tile_async<D, BQ>(base + QTILE, gb, a.do_st, qs, s - 1, wave, lane);
             }
         };
         if (total > 0) prefetch(0, 0);
 
-        // K and V fragments of this wavefront's 32 keys (B operands: column = key, k = head dim)
+        // K and V fragments of the pair's 32 keys (B operands: column = key, k = head dim)
         bf16x8 kf[KS], vf[KS];
         {
             const bool ok = kvrow < s;
@@ -120,88 +145,100 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkv_kernel(const AttnArg
                 vf[ks] = f.v;
             }
         }
-        f32x16 dkT[DB], dvT[DB];  // rows = head dim, column = key
+        f32x16 dkT[DBH], dvT[DBH];  // rows = this wavefront's half of the head dim, column = key
 #pragma unroll
-        for (int db = 0; db < DB; db++)
+        for (int d = 0; d < DBH; d++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) dkT[db][i] = dvT[db][i] = 0.f;
+            for (int i = 0; i < 16; i++) dkT[d][i] = dvT[d][i] = 0.f;
 
         auto step_fn = [&](auto bufc, int step) {
             constexpr int BUF = decltype(bufc)::value;
             const char *sQ = smem + BUF * STEP;
             const char *sG = sQ + QTILE;
-            const float *sL = (const float *)(sQ + 2 * QTILE);  // lse2[64], delta[64]
+            const int h = g * a.G + step / nsteps;
             const int q_lo = qfirst + (step % nsteps) * BQ;
+            // a block (32 queries x the pair's 32 keys) is empty when it lies past the end of the
+            // sequence or wholly above the diagonal; both wavefronts of a pair agree on that
+            auto empty = [&](int qb) {
+                const int lo_ = q_lo + qb * 32;
+                return lo_ >= s || (a.causal && lo_ + 31 < wk_lo);
+            };
             wait_vmem();
-            __syncthreads();
+            __syncthreads();  // tile `step` is in LDS; the previous step's exchange slots are free
             if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
 
-            // S = Q K^T and dP = dO V^T for one 32-query block (rows = queries, column = key)
-            auto scores = [&](int qb, f32x16 &sacc, f32x16 &pacc) {
+            // ---- phase 1: P and dS of query block j
+            uint32_t pp[8], dd[8];
+            const int my_lo = q_lo + j * 32;
+            if (!empty(j)) {
+                // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e.  (Rows past the end of the
+                // sequence read neighbouring scratch values; they are masked below.)
+                const float *lp = a.lse_in + (int64_t)h * a.T + tok0 + my_lo + 4 * hl;
+                const float *dp = a.delta_in + (int64_t)h * a.T + tok0 + my_lo + 4 * hl;
+                f32x4 l4[4], d4[4];
+#pragma unroll
+                for (int i4 = 0; i4 < 4; i4++) {
+                    l4[i4] = *(const f32x4u *)(lp + 8 * i4);
+                    d4[i4] = *(const f32x4u *)(dp + 8 * i4);
+                }
+                f32x16 sacc, pacc;
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++) {
-                    sacc = mfma32(lds_nat(sQ, qb * 32 * L::ROWB + lo.nat[ks]), kf[ks], sacc);
-                    pacc = mfma32(lds_nat(sG, qb * 32 * L::ROWB + lo.nat[ks]), vf[ks], pacc);
+                    sacc = mfma32(lds_nat(sQ, j * 32 * L::ROWB + nat[ks]), kf[ks], sacc);
+                    pacc = mfma32(lds_nat(sG, j * 32 * L::ROWB + nat[ks]), vf[ks], pacc);
                 }
-            };
-            // P = exp2(S c - lse2), dS = P (dP - delta), both rounded to bf16 operand fragments.
-            // Accumulator register 4*i4 + e is query row q_lo + 32*qb + 8*i4 + 4*hl + e.
-            auto probs = [&](int qb, const f32x16 &sacc, const f32x16 &pacc, bool masked, uint32_t (&pp)[8],
-                             uint32_t (&dd)[8]) {
+                const bool masked = (a.causal && my_lo < wk_lo + 31) || (my_lo + 32 > s);
+                auto probs = [&](auto maskc) {
+                    constexpr bool MASK = decltype(maskc)::value;
 #pragma unroll
-                for (int i4 = 0; i4 < 4; i4++) {
-                    const f32x4 l4 = *(const f32x4 *)(sL + qb * 32 + 8 * i4 + 4 * hl);
-                    const f32x4 d4 = *(const f32x4 *)(sL + 64 + qb * 32 + 8 * i4 + 4 * hl);
-                    float p[4], ds[4];
+                    for (int i4 = 0; i4 < 4; i4++) {
+                        float p[4], ds[4];
 #pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * i4 + e], a.scale_l2, -l4[e]));
-                        if (masked) {
-                            const int qr = q_lo + qb * 32 + 8 * i4 + 4 * hl + e;
-                            if ((a.causal && qr < kvrow) || qr >= s) p[e] = 0.f;
+                        for (int e = 0; e < 4; e++) {
+                            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * i4 + e], a.scale_l2, -l4[i4][e]));
+                            if (MASK) {
+                                const int qr = my_lo + 8 * i4 + 4 * hl + e;
+                                p[e] = ((a.causal && qr < kvrow) || qr >= s) ? 0.f : p[e];
+                            }
+                            ds[e] = p[e] * (pacc[4 * i4 + e] - d4[i4][e]);
                         }
-                        ds[e] = p[e] * (pacc[4 * i4 + e] - d4[e]);
+                        pp[2 * i4] = pack_bf16x2(p[0], p[1]);
+                        pp[2 * i4 + 1] = pack_bf16x2(p[2], p[3]);
+                        dd[2 * i4] = pack_bf16x2(ds[0], ds[1]);
+                        dd[2 * i4 + 1] = pack_bf16x2(ds[2], ds[3]);
                     }
-                    pp[2 * i4] = pack_bf16x2(p[0], p[1]);
-                    pp[2 * i4 + 1] = pack_bf16x2(p[2], p[3]);
-                    dd[2 * i4] = pack_bf16x2(ds[0], ds[1]);
-                    dd[2 * i4 + 1] = pack_bf16x2(ds[2], ds[3]);
-                }
-            };
-            // dV^T += dO^T P and dK^T += Q^T dS for one block
-            auto accumulate = [&](int qb, const uint32_t (&pp)[8], const uint32_t (&dd)[8]) {
+                };
+                if (masked)
+                    probs(std::true_type{});
+                else
+                    probs(std::false_type{});
+                char *slot = exch + (kb * 2 + j) * XSLOT + lane * 16;
+                *(u32x4 *)(slot) = u32x4{pp[0], pp[1], pp[2], pp[3]};
+                *(u32x4 *)(slot + 1024) = u32x4{pp[4], pp[5], pp[6], pp[7]};
+                *(u32x4 *)(slot + 2048) = u32x4{dd[0], dd[1], dd[2], dd[3]};
+                *(u32x4 *)(slot + 3072) = u32x4{dd[4], dd[5], dd[6], dd[7]};
+            }
+            __syncthreads();  // the partner's fragments are visible
+
+            // ---- phase 2: accumulate both query blocks into this wavefront's half of the head dim
+#pragma unroll
+            for (int qb = 0; qb < 2; qb++) {
+                if (empty(qb)) continue;
+                const char *slot = exch + (kb * 2 + qb) * XSLOT + lane * 16;
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++) {
                     Frag8 pf, df;
-                    pf.u = u32x4{pp[4 * hf], pp[4 * hf + 1], pp[4 * hf + 2], pp[4 * hf + 3]};
-                    df.u = u32x4{dd[4 * hf], dd[4 * hf + 1], dd[4 * hf + 2], dd[4 * hf + 3]};
+                    pf.u = *(const u32x4 *)(slot + hf * 1024);
+                    df.u = *(const u32x4 *)(slot + 2048 + hf * 1024);
                     const int rowoff = (qb * 32 + hf * 16) * L::ROWB;
 #pragma unroll
-                    for (int db = 0; db < DB; db++) {
-                        dvT[db] = mfma32(lds_tr(sG, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), pf.v, dvT[db]);
-                        dkT[db] = mfma32(lds_tr(sQ, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), df.v, dkT[db]);
+                    for (int d = 0; d < DBH; d++) {
+                        dvT[d] = mfma32(lds_tr(sG, rowoff + trw[d][0], rowoff + trw[d][1]), pf.v, dvT[d]);
+                        dkT[d] = mfma32(lds_tr(sQ, rowoff + trw[d][0], rowoff + trw[d][1]), df.v, dkT[d]);
                     }
                 }
-            };
-
-            const bool plain = (!a.causal || q_lo >= wk_lo + 31) && q_lo + BQ <= s;
-#pragma unroll
-            for (int qb = 0; qb < 2; qb++) {
-                const int qb_lo = q_lo + qb * 32;
-                if (!plain) {
-                    if (qb_lo >= s) continue;
-                    if (a.causal && qb_lo + 31 < wk_lo) continue;  // all rows before all keys
-                }
-                f32x16 s0, p0;
-                uint32_t pp0[8], dd0[8];
-                scores(qb, s0, p0);
-                if (plain)
-                    probs(qb, s0, p0, false, pp0, dd0);
-                else
-                    probs(qb, s0, p0, true, pp0, dd0);
-                accumulate(qb, pp0, dd0);
             }
         };
         for (int step = 0; step < total; step += 2) {
@@ -211,12 +248,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bwd_dkv_kernel(const AttnArg
 
         if (kvrow < s) {
             const int64_t eb = a.grad_f32 ? 4 : 2;
-            store_rowT<DB>((char *)a.dk + ((tok0 + kvrow) * a.dk_st + (int64_t)g * a.dk_sh) * eb, a.grad_f32,
-                           dkT, a.scale, hl);
-            store_rowT<DB>((char *)a.dv + ((tok0 + kvrow) * a.dv_st + (int64_t)g * a.dv_sh) * eb, a.grad_f32,
-                           dvT, 1.0f, hl);
+            const int64_t d0 = j * (D / 2);  // first head-dim element of this wavefront's half
+            store_rowT<DBH>((char *)a.dk + ((tok0 + kvrow) * a.dk_st + (int64_t)g * a.dk_sh + d0) * eb, a.grad_f32,
+                            dkT, a.scale, hl);
+            store_rowT<DBH>((char *)a.dv + ((tok0 + kvrow) * a.dv_st + (int64_t)g * a.dv_sh + d0) * eb, a.grad_f32,
+                            dvT, 1.0f, hl);
         }
-        __syncthreads();
     }
     if (tid == 0) queue_retire(a.pq);
 }
@@ -243,7 +280,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
     for (;;) {
         if (tid == 0) s_item = queue_fetch(a.pq, cursor);
         __syncthreads();
-        const int item = s_item;
+        const int item = __builtin_amdgcn_readfirstlane(s_item);  // wave-uniform: everything derived from it stays scalar
         if (item < 0) break;
         const flexsp_item it = a.pq.items[item];
         const int s = it.seq_len, h = it.head, g = h / a.G;
@@ -253,9 +290,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         const int ntiles = (kv_end + kDqBk - 1) / kDqBk;
         const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
         const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
+        const uint32_t goffk = tile_goff<D>(a.k_st, wave, lane), goffv = tile_goff<D>(a.v_st, wave, lane);
         auto prefetch = [&](int t, int buf) {
-            load_tile_async<D, kDqBk>(smem + buf * 2 * TILE, kbase, a.k_st, t * kDqBk, s - 1, wave, lane);
-            load_tile_async<D, kDqBk>(smem + buf * 2 * TILE + TILE, vbase, a.v_st, t * kDqBk, s - 1, wave, lane);
+            char *dk = smem + buf * 2 * TILE, *dv = dk + TILE;
+            if ((t + 1) * kDqBk <= s) {  // whole tile inside the sequence
+                load_tile_async_fast<D, kDqBk>(dk, kbase + (int64_t)t * kDqBk * a.k_st, a.k_st, goffk, wave);
+                load_tile_async_fast<D, kDqBk>(dv, vbase + (int64_t)t * kDqBk * a.v_st, a.v_st, goffv, wave);
+            } else {
+                load_tile_async<D, kDqBk>(dk, kbase, a.k_st, t * kDqBk, s - 1, wave, lane);
+                load_tile_async<D, kDqBk>(dv, vbase, a.v_st, t * kDqBk, s - 1, wave, lane);
+            }
         };
         prefetch(0, 0);
 

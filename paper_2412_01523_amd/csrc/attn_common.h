@@ -39,6 +39,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, t);
 }
 
+// acc + lo + hi of a packed bf16 pair (v_dot2_f32_bf16 against {1, 1}).
+__device__ __forceinline__ float add_bf16x2(uint32_t pk, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3f803f80u),
+                                           acc, false);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 
@@ -103,6 +110,31 @@ __device__ __forceinline__ void load_tile_async(char *tile, const uint16_t *g, i
         const int grow = min(first + row, last_valid);
         global_to_lds16(g + (int64_t)grow * stride + c * 8, tile + (n * kThreads + wave * 64) * 16);
     }
+}
+
+// The same copy without the clamp, for tiles that lie wholly inside the sequence.  Chunk n of a
+// lane lies kThreads/CH rows below chunk n-1 in the same (swizzled) column, because the swizzle
+// has a period of 16 rows; so one per-lane byte offset (tile_goff, computed once per item) plus
+// wave-uniform addresses describe the whole copy, and it costs no vector address arithmetic.
+template <int D>
+__device__ __forceinline__ uint32_t tile_goff(int64_t stride, int wave, int lane)
+{
+    typedef LdsTile<D> L;
+    const int pos = wave * 64 + lane;
+    const int row = pos / L::CH;
+    const int c = (pos % L::CH) ^ L::sw(row);
+    return (uint32_t)(row * (uint32_t)stride * 2u + c * 16);
+}
+template <int D, int ROWS>
+__device__ __forceinline__ void load_tile_async_fast(char *tile, const uint16_t *g_tile, int64_t stride,
+                                                     uint32_t goff, int wave)
+{
+    typedef LdsTile<D> L;
+    static_assert((kThreads / L::CH) % 16 == 0, "rows per pass must be a multiple of the swizzle period");
+#pragma unroll
+    for (int n = 0; n < ROWS * L::CH / kThreads; n++)
+        global_to_lds16((const char *)(g_tile + (int64_t)n * (kThreads / L::CH) * stride) + goff,
+                        tile + (n * kThreads + wave * 64) * 16);
 }
 
 // Per-lane byte offsets of operand fragments inside a tile (computed once per kernel).

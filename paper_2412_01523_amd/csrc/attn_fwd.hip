@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     for (;;) {
         if (tid == 0) s_item = queue_fetch(a.pq, cursor);
         __syncthreads();
-        const int item = s_item;
+        const int item = __builtin_amdgcn_readfirstlane(s_item);  // wave-uniform: everything derived from it stays scalar
         if (item < 0) break;
         const flexsp_item it = a.pq.items[item];
         const int s = it.seq_len, h = it.head, g = h / a.G;
@@ -52,9 +52,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
         const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
 
+        const uint32_t goffk = tile_goff<D>(a.k_st, wave, lane), goffv = tile_goff<D>(a.v_st, wave, lane);
         auto prefetch = [&](int t, int buf) {
-            load_tile_async<D, kFwdBk>(smem + buf * 2 * TILE, kbase, a.k_st, t * kFwdBk, s - 1, wave, lane);
-            load_tile_async<D, kFwdBk>(smem + buf * 2 * TILE + TILE, vbase, a.v_st, t * kFwdBk, s - 1, wave, lane);
+            char *dk = smem + buf * 2 * TILE, *dv = dk + TILE;
+            if ((t + 1) * kFwdBk <= s) {  // whole tile inside the sequence
+                load_tile_async_fast<D, kFwdBk>(dk, kbase + (int64_t)t * kFwdBk * a.k_st, a.k_st, goffk, wave);
+                load_tile_async_fast<D, kFwdBk>(dv, vbase + (int64_t)t * kFwdBk * a.v_st, a.v_st, goffv, wave);
+            } else {
+                load_tile_async<D, kFwdBk>(dk, kbase, a.k_st, t * kFwdBk, s - 1, wave, lane);
+                load_tile_async<D, kFwdBk>(dv, vbase, a.v_st, t * kFwdBk, s - 1, wave, lane);
+            }
         };
         prefetch(0, 0);
 
@@ -138,7 +145,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                 for (int i = 0; i < 16; i += 2) {
                     float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i], a.scale_l2, -moff));
                     float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i + 1], a.scale_l2, -moff));
-                    psum += p0 + p1;
+                    psum += p0 + p1;  // fp32: the log-sum-exp feeds the backward recomputation
                     pk[kb][i >> 1] = pack_bf16x2(p0, p1);
                 }
             l_run += psum;

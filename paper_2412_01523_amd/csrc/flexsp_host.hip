@@ -356,7 +356,7 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
         }
         size_t head_bytes = off;
         size_t delta_off = off;
-        off = align(off + p->delta_bytes);
+        off = align(off + p->delta_bytes + 512);  // the dK/dV kernel reads up to 63 floats past a row's end
         hipError_t e = hipSetDevice(ctx->device);
         if (e == hipSuccess) e = hipMalloc(&p->dev_base, off ? off : 256);
         if (e != hipSuccess) {
@@ -551,7 +551,7 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
     a.pq = plan->dq[FLEXSP_PASS_BWD_DKV];
     {
         Timed tm(ctx, FLEXSP_K_BWD_DKV, s);
-        e = launch_attn_bwd_dkv(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DKV], 1), s);
+        e = launch_attn_bwd_dkv(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DKV], 2), s);
     }
     if (e != hipSuccess) return hip_fail(e);
     a.pq = plan->dq[FLEXSP_PASS_BWD_DQ];

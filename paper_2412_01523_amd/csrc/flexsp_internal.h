@@ -14,7 +14,7 @@ constexpr int kFwdBq = 128;    // query rows per forward work item (4 waves x 32
 constexpr int kFwdBk = 64;     // key rows staged in LDS per forward step
 constexpr int kDqBq = 128;     // query rows per dQ work item
 constexpr int kDqBk = 64;      // key rows per dQ step
-constexpr int kDkvBk = 128;    // key rows per dK/dV work item (4 waves x 32 rows)
+constexpr int kDkvBk = 64;     // key rows per dK/dV work item (2 pairs of waves x 32 rows)
 constexpr int kDkvBq = 64;     // query rows per dK/dV step
 constexpr int kThreads = 256;  // every attention kernel runs 4 wavefronts per workgroup
 constexpr int kMaxQueues = 8;  // one work queue per XCD

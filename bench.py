@@ -189,6 +189,17 @@ def main() -> int:
             nbytes = 2 * Tp * Hp_tot * c1.d * 2
             res[which] = {"avg_ms": ms / n, "GBps": nbytes / (ms / n * 1e-3) / 1e9,
                           "frac_of_hbm_peak": nbytes / (ms / n * 1e-3) / HBM_PEAK}
+        # the same kernel with P = 1 is a plain copy: the ceiling this permute can reach
+        one = dsts[0].view(1, Tp, Hp_tot, c1.d)
+        for i in range(10):
+            fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf].view(1, Tp, Hp_tot, c1.d), 1, stream)
+        ctx.profile_start(64)
+        for i in range(40):
+            fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf].view(1, Tp, Hp_tot, c1.d), 1, stream)
+        pr = ctx.profile_stop()
+        ms, n = pr["pack"]
+        res["plain_copy_same_kernel"] = {"avg_ms": ms / n, "GBps": 2 * Tp * Hp_tot * c1.d * 2 / (ms / n * 1e-3) / 1e9}
+        del one
         out["permute"] = {"shape": [Tp, Hp_tot, c1.d], "sp_degree": Pp, "dtype": "bf16",
                           "bytes_per_call": 2 * Tp * Hp_tot * c1.d * 2, "buffers_rotated": nbuf,
                           "peak_GBps": HBM_PEAK / 1e9, **res}

@@ -1,10 +1,12 @@
 // Layout permute kernels: sequence-sharded [T, H, D] <-> head-sharded [P, T, H/P, D]
 // (the local half of the exchanges in paper Sec. 2.1.2, Eq. 2 and Eq. 4).
 //
-// HBM-bound bit copy.  The head-sharded side is walked linearly, so one side of every
-// access is perfectly contiguous and the other side is contiguous in runs of
-// (H/P)*D*elem_bytes bytes (1 KiB for 4 heads x 128 x bf16: one 16-byte access per lane of
-// a wavefront).  Each thread keeps UNROLL independent 16-byte loads in flight.
+// HBM-bound bit copy.  The SEQUENCE-sharded side is walked linearly, so one side of every access
+// is perfectly contiguous and the other side splits into P streams (one per slab), each
+// contiguous in runs of (H/P)*D*elem_bytes bytes (1 KiB for 4 heads x 128 x bf16: one 16-byte
+// access per lane of a wavefront).  Walking the head-sharded side instead would make every
+// workgroup that runs at the same time read the same 1/P-wide window of each token row, which
+// concentrates the traffic on a fraction of the memory channels.
 #include "flexsp_internal.h"
 
 namespace flexsp {
@@ -20,69 +22,77 @@ template <> struct VecOf<2> { typedef uint16_t type; };
 template <> struct VecOf<1> { typedef uint8_t type; };
 
 constexpr int kPackThreads = 256;
-constexpr int kPackUnroll = 8;
 
 // Units are vectors of VB bytes.  rc = vectors per (token, slab) run, row = vectors per
-// token on the sequence-sharded side (= P * rc), slab = T * rc vectors per slab.
-// rc_shift >= 0 when rc is a power of two.
-template <int VB, bool UNPACK>
+// token on the sequence-sharded side (= P * rc), slab = T * rc vectors per slab.  One vector
+// per thread and one 4 KiB stretch per workgroup measured fastest (more vectors per thread
+// lose 5-15 %).  IDX is the integer type of a vector index (32-bit whenever the tensor has
+// fewer than 2^31 vectors); shifts replace the divisions when rc and row are powers of two.
+template <int VB, bool UNPACK, typename IDX>
 __global__ __launch_bounds__(kPackThreads) void permute_kernel(
     const typename VecOf<VB>::type *__restrict__ src, typename VecOf<VB>::type *__restrict__ dst,
-    int64_t total, int64_t slab, int64_t row, int32_t rc, int32_t rc_shift)
+    IDX total, IDX slab, IDX row, IDX rc, int row_shift, int rc_shift)
+{
+    const IDX c = (IDX)blockIdx.x * kPackThreads + threadIdx.x;  // sequence-sharded index
+    if (c >= total) return;
+    IDX t, e, r, w;
+    if (row_shift >= 0) {
+        t = c >> row_shift;
+        e = c & (row - 1);
+    } else {
+        t = c / row;  // token
+        e = c - t * row;
+    }
+    if (rc_shift >= 0) {
+        r = e >> rc_shift;
+        w = e & (rc - 1);
+    } else {
+        r = e / rc;  // slab (peer)
+        w = e - r * rc;
+    }
+    const IDX o = r * slab + t * rc + w;  // head-sharded index
+    if (UNPACK)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(&src[o]), &dst[c]);
+    else
+        __builtin_nontemporal_store(__builtin_nontemporal_load(&src[c]), &dst[o]);
+}
+
+inline int shift_of(int64_t x)
+{
+    if (x <= 0 || (x & (x - 1)) != 0) return -1;
+    int sft = 0;
+    while (((int64_t)1 << sft) < x) sft++;
+    return sft;
+}
+
+template <int VB, typename IDX>
+hipError_t launch_idx(const void *src, void *dst, int64_t total, int64_t slab, int64_t row, int64_t rc,
+                      bool unpack, hipStream_t s)
 {
     typedef typename VecOf<VB>::type V;
-    const int64_t tile = (int64_t)kPackThreads * kPackUnroll;
-    for (int64_t base = (int64_t)blockIdx.x * tile; base < total; base += (int64_t)gridDim.x * tile) {
-        int64_t lin[kPackUnroll], str[kPackUnroll];
-        V val[kPackUnroll];
-#pragma unroll
-        for (int u = 0; u < kPackUnroll; u++) {
-            int64_t c = base + (int64_t)u * kPackThreads + threadIdx.x;  // head-sharded index
-            lin[u] = c;
-            int64_t r = c / slab;  // slab (peer) index
-            int64_t e = c - r * slab;
-            int64_t t, w;
-            if (rc_shift >= 0) {
-                t = e >> rc_shift;
-                w = e & (rc - 1);
-            } else {
-                t = e / rc;
-                w = e - t * rc;
-            }
-            str[u] = t * row + r * rc + w;  // sequence-sharded index
-        }
-#pragma unroll
-        for (int u = 0; u < kPackUnroll; u++)
-            if (lin[u] < total) val[u] = __builtin_nontemporal_load(&src[UNPACK ? lin[u] : str[u]]);
-#pragma unroll
-        for (int u = 0; u < kPackUnroll; u++)
-            if (lin[u] < total) __builtin_nontemporal_store(val[u], &dst[UNPACK ? str[u] : lin[u]]);
-    }
+    int64_t blocks = (total + kPackThreads - 1) / kPackThreads;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    if (unpack)
+        hipLaunchKernelGGL((permute_kernel<VB, true, IDX>), dim3((unsigned)blocks), dim3(kPackThreads), 0, s,
+                           (const V *)src, (V *)dst, (IDX)total, (IDX)slab, (IDX)row, (IDX)rc, shift_of(row),
+                           shift_of(rc));
+    else
+        hipLaunchKernelGGL((permute_kernel<VB, false, IDX>), dim3((unsigned)blocks), dim3(kPackThreads), 0, s,
+                           (const V *)src, (V *)dst, (IDX)total, (IDX)slab, (IDX)row, (IDX)rc, shift_of(row),
+                           shift_of(rc));
+    return hipGetLastError();
 }
 
 template <int VB>
 hipError_t launch_vb(const void *src, void *dst, int64_t bytes, int64_t T, int64_t run_bytes, int P,
                      bool unpack, hipStream_t s)
 {
-    typedef typename VecOf<VB>::type V;
     int64_t total = bytes / VB;
-    int32_t rc = (int32_t)(run_bytes / VB);
-    int32_t shift = -1;
-    if ((rc & (rc - 1)) == 0) {
-        shift = 0;
-        while ((1 << shift) < rc) shift++;
-    }
+    int64_t rc = run_bytes / VB;
     int64_t slab = T * rc, row = (int64_t)P * rc;
-    int64_t tile = (int64_t)kPackThreads * kPackUnroll;
-    int64_t blocks = (total + tile - 1) / tile;
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    if (unpack)
-        hipLaunchKernelGGL((permute_kernel<VB, true>), dim3((unsigned)blocks), dim3(kPackThreads), 0, s,
-                           (const V *)src, (V *)dst, total, slab, row, rc, shift);
-    else
-        hipLaunchKernelGGL((permute_kernel<VB, false>), dim3((unsigned)blocks), dim3(kPackThreads), 0, s,
-                           (const V *)src, (V *)dst, total, slab, row, rc, shift);
-    return hipGetLastError();
+    if (total + kPackThreads < ((int64_t)1 << 31))
+        return launch_idx<VB, uint32_t>(src, dst, total, slab, row, rc, unpack, s);
+    return launch_idx<VB, int64_t>(src, dst, total, slab, row, rc, unpack, s);
 }
 
 }  // namespace

@@ -71,22 +71,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
     constexpr int QTILE = BQ * L::ROWB;
     constexpr int STEP = 2 * QTILE;             // Q | dO
     constexpr int XSLOT = 4096;                 // P (2 KB) and dS (2 KB) of one 32 x 32 block
-    // [buffer][Q | dO] then 4 exchange slots; the first word of the exchange area doubles as the
-    // item broadcast slot between items
+    // [buffer][Q | dO] then 4 exchange slots
     __shared__ __attribute__((aligned(1024))) char smem[2 * STEP + 4 * XSLOT];
     char *const exch = smem + 2 * STEP;
-    volatile int *const s_item = (volatile int *)exch;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
+    const int lane0 = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = wave >> 1, j = wave & 1;     // key block, role inside the pair
-    const int r = lane & 31, hl = lane >> 5;
     int nat[KS];                                // natural-read offsets, as in LaneOffsets
     int trw[DBH][2];                            // transpose-read offsets of this wavefront's head-dim blocks
     {
         LaneOffsets<D> lo;
-        lo.init(lane);
+        lo.init(lane0);
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) nat[ks] = lo.nat[ks];
 #pragma unroll
@@ -94,15 +91,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
 #pragma unroll
             for (int h = 0; h < 2; h++) trw[d][h] = j ? lo.tr[DBH + d][h] : lo.tr[d][h];
     }
-    int cursor = 0;
+    ItemDealer deal;
+    deal.init(a.pq);
 
-    for (;;) {
-        __syncthreads();  // the exchange area is free again
-        if (tid == 0) *s_item = queue_fetch(a.pq, cursor);
-        __syncthreads();
-        const int item = __builtin_amdgcn_readfirstlane(*s_item);  // wave-uniform: everything derived from it stays scalar
-        if (item < 0) break;
+    for (int item = deal.next(); item >= 0; item = deal.next()) {
         const flexsp_item it = a.pq.items[item];
+        // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
+        // the item instead of being hoisted out of this loop into long-lived registers
+        int lane = lane0;
+        asm volatile("" : "+v"(lane));
+        const int r = lane & 31, hl = lane >> 5;
         const int s = it.seq_len, g = it.head;
         const int kv0 = it.tile * kDkvBk;
         const int64_t tok0 = it.seq_start;
@@ -163,6 +161,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 const int lo_ = q_lo + qb * 32;
                 return lo_ >= s || (a.causal && lo_ + 31 < wk_lo);
             };
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) asm volatile("" : "+v"(nat[ks]));  // see LaneOffsets::pin
+#pragma unroll
+            for (int d = 0; d < DBH; d++) {
+                asm volatile("" : "+v"(trw[d][0]));
+                asm volatile("" : "+v"(trw[d][1]));
+            }
             wait_vmem();
             __syncthreads();  // tile `step` is in LDS; the previous step's exchange slots are free
             if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
@@ -246,16 +251,26 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             if (step + 1 < total) step_fn(std::integral_constant<int, 1>{}, step + 1);
         }
 
-        if (kvrow < s) {
-            const int64_t eb = a.grad_f32 ? 4 : 2;
-            const int64_t d0 = j * (D / 2);  // first head-dim element of this wavefront's half
-            store_rowT<DBH>((char *)a.dk + ((tok0 + kvrow) * a.dk_st + (int64_t)g * a.dk_sh + d0) * eb, a.grad_f32,
-                            dkT, a.scale, hl);
-            store_rowT<DBH>((char *)a.dv + ((tok0 + kvrow) * a.dv_st + (int64_t)g * a.dv_sh + d0) * eb, a.grad_f32,
-                            dvT, 1.0f, hl);
+        const int64_t d0 = j * (D / 2);  // first head-dim element of this wavefront's half
+        if (a.grad_f32) {
+            if (kvrow < s) {
+                store_rowT<DBH>((char *)a.dk + ((tok0 + kvrow) * a.dk_st + (int64_t)g * a.dk_sh + d0) * 4, true, dkT,
+                                a.scale, hl);
+                store_rowT<DBH>((char *)a.dv + ((tok0 + kvrow) * a.dv_st + (int64_t)g * a.dv_sh + d0) * 4, true, dvT,
+                                1.0f, hl);
+            }
+        } else if (wk_lo < s) {
+            // through the Q/dO buffer the last step did not use: 2 x 32 half-rows per wavefront
+            char *stage = smem + (total & 1) * STEP + wave * (2 * 32 * (D / 2) * 2);
+            const int nrows = min(32, s - wk_lo);
+            store_rowT_bf16_lds<DBH>(stage, (uint16_t *)a.dk + (tok0 + wk_lo) * a.dk_st + (int64_t)g * a.dk_sh + d0,
+                                     a.dk_st, nrows, dkT, a.scale, lane);
+            store_rowT_bf16_lds<DBH>(stage + 32 * (D / 2) * 2,
+                                     (uint16_t *)a.dv + (tok0 + wk_lo) * a.dv_st + (int64_t)g * a.dv_sh + d0, a.dv_st,
+                                     nrows, dvT, 1.0f, lane);
         }
+        barrier_lds_only();  // the tiles and the exchange slots are reused by the next item
     }
-    if (tid == 0) queue_retire(a.pq);
 }
 
 // ------------------------------------------------------------------------------ dQ
@@ -267,22 +282,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
     constexpr int DB = D / 32;
     constexpr int TILE = kDqBk * L::ROWB;
     __shared__ __attribute__((aligned(1024))) char smem[4 * TILE];  // [buffer][K | V]
-    __shared__ int s_item;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
+    const int lane0 = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r = lane & 31, hl = lane >> 5;
     LaneOffsets<D> lo;
-    lo.init(lane);
-    int cursor = 0;
+    lo.init(lane0);
+    ItemDealer deal;
+    deal.init(a.pq);
 
-    for (;;) {
-        if (tid == 0) s_item = queue_fetch(a.pq, cursor);
-        __syncthreads();
-        const int item = __builtin_amdgcn_readfirstlane(s_item);  // wave-uniform: everything derived from it stays scalar
-        if (item < 0) break;
+    for (int item = deal.next(); item >= 0; item = deal.next()) {
         const flexsp_item it = a.pq.items[item];
+        // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
+        // the item instead of being hoisted out of this loop into long-lived registers
+        int lane = lane0;
+        asm volatile("" : "+v"(lane));
+        const int r = lane & 31, hl = lane >> 5;
         const int s = it.seq_len, h = it.head, g = h / a.G;
         const int q0 = it.tile * kDqBq;
         const int64_t tok0 = it.seq_start;
@@ -334,65 +349,74 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
             const char *sK = smem + BUF * 2 * TILE;
             const char *sV = sK + TILE;
             const int kv0 = t * kDqBk;
+            lo.pin();
             wait_vmem();
             __syncthreads();
             if (t + 1 < ntiles) prefetch(t + 1, BUF ^ 1);
             if (a.causal && kv0 > wq_lo + 31) return;
 
-            f32x16 sacc[2], pacc[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) sacc[kb][i] = pacc[kb][i] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++)
-#pragma unroll
-                for (int kb = 0; kb < 2; kb++) {
-                    sacc[kb] = mfma32(lds_nat(sK, kb * 32 * L::ROWB + lo.nat[ks]), qf[ks], sacc[kb]);
-                    pacc[kb] = mfma32(lds_nat(sV, kb * 32 * L::ROWB + lo.nat[ks]), gf[ks], pacc[kb]);
-                }
             const bool need_mask = a.causal ? (kv0 + kDqBk - 1 > wq_lo) : (kv0 + kDqBk > s);
             const int lim = a.causal ? qrow : s - 1;
-            uint32_t dd[2][8];
+            // one 32-key block at a time (keeps the register count under half the file)
 #pragma unroll
-            for (int kb = 0; kb < 2; kb++)
+            for (int kb = 0; kb < 2; kb++) {
+                if (a.causal && kv0 + kb * 32 > wq_lo + 31) continue;  // block wholly above the diagonal
+                f32x16 sacc, pacc;
 #pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i], a.scale_l2, -lse2));
-                    float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i + 1], a.scale_l2, -lse2));
-                    if (need_mask) {
-                        int kv = kv0 + kb * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
-                        if (kv > lim) p0 = 0.f;
-                        if (kv + 1 > lim) p1 = 0.f;
-                    }
-                    dd[kb][i >> 1] = pack_bf16x2(p0 * (pacc[kb][i] - delta), p1 * (pacc[kb][i + 1] - delta));
+                for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) {
+                    sacc = mfma32(lds_nat(sK, kb * 32 * L::ROWB + lo.nat[ks]), qf[ks], sacc);
+                    pacc = mfma32(lds_nat(sV, kb * 32 * L::ROWB + lo.nat[ks]), gf[ks], pacc);
                 }
-            // dQ^T += K^T dS^T
+                uint32_t dd[8];
+                auto dsfn = [&](auto maskc) {
+                    constexpr bool MASK = decltype(maskc)::value;
 #pragma unroll
-            for (int kb = 0; kb < 2; kb++)
+                    for (int i = 0; i < 16; i += 2) {
+                        float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], a.scale_l2, -lse2));
+                        float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i + 1], a.scale_l2, -lse2));
+                        if (MASK) {
+                            const int kv = kv0 + kb * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
+                            p0 = kv > lim ? 0.f : p0;
+                            p1 = kv + 1 > lim ? 0.f : p1;
+                        }
+                        dd[i >> 1] = pack_bf16x2(p0 * (pacc[i] - delta), p1 * (pacc[i + 1] - delta));
+                    }
+                };
+                if (need_mask)
+                    dsfn(std::true_type{});
+                else
+                    dsfn(std::false_type{});
+                // dQ^T += K^T dS^T
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++) {
                     Frag8 df;
-                    df.u = u32x4{dd[kb][4 * hf], dd[kb][4 * hf + 1], dd[kb][4 * hf + 2], dd[kb][4 * hf + 3]};
+                    df.u = u32x4{dd[4 * hf], dd[4 * hf + 1], dd[4 * hf + 2], dd[4 * hf + 3]};
                     const int rowoff = (kb * 32 + hf * 16) * L::ROWB;
 #pragma unroll
                     for (int db = 0; db < DB; db++)
                         dqT[db] = mfma32(lds_tr(sK, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), df.v, dqT[db]);
                 }
+            }
         };
         for (int t = 0; t < ntiles; t += 2) {
             step_fn(std::integral_constant<int, 0>{}, t);
             if (t + 1 < ntiles) step_fn(std::integral_constant<int, 1>{}, t + 1);
         }
 
-        if (qok) {
-            const int64_t eb = a.grad_f32 ? 4 : 2;
-            store_rowT<DB>((char *)a.dq + ((tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh) * eb, a.grad_f32,
-                           dqT, a.scale, hl);
+        if (a.grad_f32) {
+            if (qok)
+                store_rowT<DB>((char *)a.dq + ((tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh) * 4, true, dqT,
+                               a.scale, hl);
+        } else if (wq_lo < s) {
+            // through the tile buffer the last step did not use (see the forward kernel)
+            store_rowT_bf16_lds<DB>(smem + (ntiles & 1) * 2 * TILE + wave * (32 * L::ROWB),
+                                    (uint16_t *)a.dq + (tok0 + wq_lo) * a.dq_st + (int64_t)h * a.dq_sh, a.dq_st,
+                                    min(32, s - wq_lo), dqT, a.scale, lane);
         }
-        __syncthreads();
+        barrier_lds_only();  // the LDS buffers are reused by the next item
     }
-    if (tid == 0) queue_retire(a.pq);
 }
 
 }  // namespace

@@ -91,12 +91,19 @@ __device__ __forceinline__ void global_to_lds4(const void *g, void *lds)
 }
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0)
 
+// Workgroup barrier that does NOT wait for this wavefront's outstanding global stores.  Used at
+// the end of a work item, where __syncthreads() would stall every wavefront until the item's
+// output rows have been acknowledged by memory (microseconds).  It orders LDS use only: a
+// wavefront reaches it after the matrix instructions that consumed its last LDS reads were
+// issued, so those reads have completed, and the next item may overwrite the tiles.
+__device__ __forceinline__ void barrier_lds_only() { __builtin_amdgcn_s_barrier(); }
+
 // Copies ROWS rows of a row-major global matrix (row r at g + r*stride elements, D bf16 each)
 // into a swizzled LDS tile, asynchronously, with all 256 threads.  Row `first + r` is clamped to
 // `last_valid`, so rows past the end of a sequence duplicate its last row (finite data; callers
 // mask them).
 template <int D, int ROWS>
-__device__ __forceinline__ void load_tile_async(char *tile, const uint16_t *g, int64_t stride, int first,
+__device__ __forceinline__ void load_tile_async(char *tile, const uint16_t *g, int32_t stride, int first,
                                                 int last_valid, int wave, int lane)
 {
     typedef LdsTile<D> L;
@@ -117,7 +124,7 @@ __device__ __forceinline__ void load_tile_async(char *tile, const uint16_t *g, i
 // has a period of 16 rows; so one per-lane byte offset (tile_goff, computed once per item) plus
 // wave-uniform addresses describe the whole copy, and it costs no vector address arithmetic.
 template <int D>
-__device__ __forceinline__ uint32_t tile_goff(int64_t stride, int wave, int lane)
+__device__ __forceinline__ uint32_t tile_goff(int32_t stride, int wave, int lane)
 {
     typedef LdsTile<D> L;
     const int pos = wave * 64 + lane;
@@ -126,7 +133,7 @@ __device__ __forceinline__ uint32_t tile_goff(int64_t stride, int wave, int lane
     return (uint32_t)(row * (uint32_t)stride * 2u + c * 16);
 }
 template <int D, int ROWS>
-__device__ __forceinline__ void load_tile_async_fast(char *tile, const uint16_t *g_tile, int64_t stride,
+__device__ __forceinline__ void load_tile_async_fast(char *tile, const uint16_t *g_tile, int32_t stride,
                                                      uint32_t goff, int wave)
 {
     typedef LdsTile<D> L;
@@ -149,6 +156,20 @@ template <int D>
 struct LaneOffsets {
     int nat[D / 16];
     int tr[D / 32][2];
+    // Makes the offsets opaque to the optimiser at this point.  Called once per tile step: the
+    // addresses of a step are then "offset register + compile-time constant", which folds into the
+    // LDS instructions' immediate field, instead of being hoisted out of the tile loop as dozens
+    // of precomputed address registers.  Emits no instruction.
+    __device__ __forceinline__ void pin()
+    {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ks++) asm volatile("" : "+v"(nat[ks]));
+#pragma unroll
+        for (int db = 0; db < D / 32; db++) {
+            asm volatile("" : "+v"(tr[db][0]));
+            asm volatile("" : "+v"(tr[db][1]));
+        }
+    }
     __device__ __forceinline__ void init(int lane)
     {
         typedef LdsTile<D> L;
@@ -231,34 +252,70 @@ __device__ __forceinline__ void store_rowT(void *row, bool f32, const f32x16 (&a
         }
 }
 
-// Work queue: one queue per XCD.  Workgroup w starts on queue w % nq (workgroups are
-// dispatched round-robin over the XCDs, so that is its own XCD's queue) and moves on to the
-// next queue when one runs dry.  Returns the item index or -1 when every queue is empty.
-// `cursor` counts how many queues this workgroup has exhausted.
-__device__ __forceinline__ int queue_fetch(const PassQueues &pq, int &cursor)
+// Epilogue store of a transposed accumulator as bf16 THROUGH LDS, so that global memory sees
+// whole 16-byte pieces of contiguous rows instead of 8-byte pieces scattered over 32 rows (which
+// the address coalescer handles one lane at a time: thousands of cycles per item).
+//   acc      NB blocks; lane l holds token row l % 32, head-dim elements db*32 + 8*i4 + 4*hl + e
+//   stage    wave-private LDS, 32 rows x ROWB bytes (ROWB = NB*64); chunk c of row r is kept at
+//            position c ^ (r & (CH-1)) so that the column-wise writes spread over the banks
+//   g        address of the first token row (this wavefront's row 0) + first head-dim element
+//   stride   token stride in elements;  nrows  rows of this wavefront inside the sequence
+template <int NB>
+__device__ __forceinline__ void store_rowT_bf16_lds(char *stage, uint16_t *g, int64_t stride, int nrows,
+                                                    const f32x16 (&acc)[NB], float mul, int lane)
 {
-    while (cursor < pq.nq) {
-        int qx = (int)((blockIdx.x + cursor) % pq.nq);
-        int begin = pq.offsets[qx], end = pq.offsets[qx + 1];
-        if (begin < end) {
-            int got = atomicAdd(&pq.counters[qx], 1);
-            if (begin + got < end) return begin + got;
+    constexpr int ROWB = NB * 64;   // bytes per staged row
+    constexpr int CH = ROWB / 16;   // 16-byte chunks per row
+    // opaque copy: keeps the address arithmetic below here, inside the epilogue, instead of being
+    // hoisted to the top of the kernel where its results would occupy registers for good
+    asm volatile("" : "+v"(lane));
+    const int r = lane & 31, hl = lane >> 5;
+#pragma unroll
+    for (int db = 0; db < NB; db++)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; i4++) {
+            u32x2 w;
+            w[0] = pack_bf16x2(acc[db][4 * i4] * mul, acc[db][4 * i4 + 1] * mul);
+            w[1] = pack_bf16x2(acc[db][4 * i4 + 2] * mul, acc[db][4 * i4 + 3] * mul);
+            const int c = (4 * db + i4) ^ (r & (CH - 1));
+            *(u32x2 *)(stage + r * ROWB + c * 16 + 8 * hl) = w;
         }
-        cursor++;
+    // the wavefront reads back what it wrote: no barrier, just LDS ordering within the wave
+#pragma unroll
+    for (int n = 0; n < 32 * CH / 64; n++) {
+        const int pos = n * 64 + lane;
+        const int row = pos / CH;
+        const int c = (pos % CH) ^ (row & (CH - 1));
+        const u32x4 v = *(const u32x4 *)(stage + pos * 16);
+        if (row < nrows) *(u32x4 *)(g + (int64_t)row * stride + c * 8) = v;
     }
-    return -1;
 }
 
-// Called by one thread of every workgroup after its last fetch.  The last workgroup to
-// arrive puts all counters back to zero, so the plan is ready for the next launch.
-__device__ __forceinline__ void queue_retire(const PassQueues &pq)
-{
-    __threadfence();
-    int done = atomicAdd(&pq.counters[pq.nq], 1);
-    if (done == (int)gridDim.x - 1) {
-        for (int x = 0; x <= pq.nq; x++) atomicExch(&pq.counters[x], 0);
-        __threadfence();
+// Work distribution.  The plan holds one longest-first item list per XCD, balanced on the host.
+// Workgroup w runs on XCD w % nq (workgroups are dispatched round-robin over the XCDs) and is
+// the (w / nq)-th of the W = gridDim / nq workgroups there.  The list is dealt to those W
+// workgroups in snake order (round 0: 0..W-1, round 1: W-1..0, ...), which is longest-processing-
+// time-first scheduling done ahead of time: every workgroup knows its items without touching a
+// shared counter (fetching through one atomic per item made 64 workgroups queue up on the same
+// address at every item boundary), and can fetch the next descriptor while it works.
+struct ItemDealer {
+    int begin, end, W, l, round;
+    __device__ __forceinline__ void init(const PassQueues &pq)
+    {
+        const int x = (int)(blockIdx.x % pq.nq);
+        W = (int)(gridDim.x / pq.nq);
+        l = (int)(blockIdx.x / pq.nq);
+        begin = pq.offsets[x];
+        end = pq.offsets[x + 1];
+        round = 0;
     }
-}
+    // index of this workgroup's next item, or -1 when its share is done
+    __device__ __forceinline__ int next()
+    {
+        const int idx = begin + round * W + ((round & 1) ? (W - 1 - l) : l);
+        round++;
+        return idx < end ? idx : -1;
+    }
+};
 
 }  // namespace flexsp

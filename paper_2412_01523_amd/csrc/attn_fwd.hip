@@ -28,22 +28,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     constexpr int TILE = kFwdBk * L::ROWB;      // bytes of one 64-row tile
     // [buffer][K | V]
     __shared__ __attribute__((aligned(1024))) char smem[4 * TILE];
-    __shared__ int s_item;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
+    const int lane0 = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int r = lane & 31, hl = lane >> 5;
     LaneOffsets<D> lo;
-    lo.init(lane);
-    int cursor = 0;
+    lo.init(lane0);
+    ItemDealer deal;
+    deal.init(a.pq);
 
-    for (;;) {
-        if (tid == 0) s_item = queue_fetch(a.pq, cursor);
-        __syncthreads();
-        const int item = __builtin_amdgcn_readfirstlane(s_item);  // wave-uniform: everything derived from it stays scalar
-        if (item < 0) break;
+    for (int item = deal.next(); item >= 0; item = deal.next()) {
         const flexsp_item it = a.pq.items[item];
+        // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
+        // the item instead of being hoisted out of this loop into long-lived registers
+        int lane = lane0;
+        asm volatile("" : "+v"(lane));
+        const int r = lane & 31, hl = lane >> 5;
         const int s = it.seq_len, h = it.head, g = h / a.G;
         const int q0 = it.tile * kFwdBq;
         const int64_t tok0 = it.seq_start;
@@ -92,6 +92,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             const char *sK = smem + BUF * 2 * TILE;
             const char *sV = sK + TILE;
             const int kv0 = t * kFwdBk;
+            lo.pin();
             wait_vmem();      // this wavefront's share of tile t has landed
             __syncthreads();  // everybody's has, and everybody is done with tile t-1
             if (t + 1 < ntiles) prefetch(t + 1, BUF ^ 1);
@@ -170,13 +171,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
 
         // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
         const float l_tot = halves_sum(l_run);
-        if (qrow < s) {
-            store_rowT<DB>(a.out_o + (tok0 + qrow) * a.o_st + (int64_t)h * a.o_sh, false, oacc, 1.0f / l_tot, hl);
-            if (hl == 0) a.lse_out[(int64_t)h * a.T + tok0 + qrow] = m_run * a.scale + __logf(l_tot);
-        }
-        __syncthreads();  // s_item and the LDS buffers are reused by the next item
+        if (qrow < s && hl == 0) a.lse_out[(int64_t)h * a.T + tok0 + qrow] = m_run * a.scale + __logf(l_tot);
+        // O goes out through the tile buffer the last step did not use (every wavefront is past the
+        // barrier of the last step, so nobody reads that buffer any more)
+        if (wq_lo < s)
+            store_rowT_bf16_lds<DB>(smem + (ntiles & 1) * 2 * TILE + wave * (32 * L::ROWB),
+                                    a.out_o + (tok0 + wq_lo) * a.o_st + (int64_t)h * a.o_sh, a.o_st,
+                                    min(32, s - wq_lo), oacc, 1.0f / l_tot, lane);
+        barrier_lds_only();  // the LDS buffers are reused by the next item
     }
-    if (tid == 0) queue_retire(a.pq);
 }
 
 }  // namespace

@@ -140,18 +140,50 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
         queue_of[g] = best;
         load[best] += group_cost[g];
     }
-    std::stable_sort(work.begin(), work.end(), [&](const Work &a, const Work &b) {
-        int qa = queue_of[a.group], qb = queue_of[b.group];
-        if (qa != qb) return qa < qb;
-        return a.cost > b.cost;
+    // item -> queue: its group's queue, then level the queues by moving the cheapest items of the
+    // fullest queue to the emptiest one (a group that outweighs a whole queue's share, e.g. one
+    // dominant sequence with few heads, is split this way; only the moved items lose L2 affinity)
+    std::vector<int32_t> item_queue(work.size());
+    for (size_t i = 0; i < work.size(); i++) item_queue[i] = queue_of[work[i].group];
+    {
+        std::vector<std::vector<int32_t>> members(nq);
+        for (size_t i = 0; i < work.size(); i++) members[item_queue[i]].push_back((int32_t)i);
+        for (int x = 0; x < nq; x++)  // cheapest last
+            std::stable_sort(members[x].begin(), members[x].end(),
+                             [&](int32_t a, int32_t b) { return work[a].cost > work[b].cost; });
+        for (size_t guard = 0; guard < work.size(); guard++) {
+            int hi = 0, lo_ = 0;
+            for (int x = 1; x < nq; x++) {
+                if (load[x] > load[hi]) hi = x;
+                if (load[x] < load[lo_]) lo_ = x;
+            }
+            if (members[hi].empty()) break;
+            const int32_t cand = members[hi].back();
+            const int64_t c = work[cand].cost;
+            if (load[hi] - c < load[lo_] + c) break;  // moving would not narrow the gap
+            members[hi].pop_back();
+            load[hi] -= c;
+            load[lo_] += c;
+            item_queue[cand] = lo_;
+            // keep the receiving queue ordered (cheapest last)
+            auto pos = std::upper_bound(members[lo_].begin(), members[lo_].end(), cand,
+                                        [&](int32_t a, int32_t b) { return work[a].cost > work[b].cost; });
+            members[lo_].insert(pos, cand);
+        }
+    }
+    std::vector<int32_t> perm(work.size());
+    for (size_t i = 0; i < perm.size(); i++) perm[i] = (int32_t)i;
+    std::stable_sort(perm.begin(), perm.end(), [&](int32_t a, int32_t b) {
+        if (item_queue[a] != item_queue[b]) return item_queue[a] < item_queue[b];
+        return work[a].cost > work[b].cost;
     });
     out.items.resize(work.size());
     for (int x = 0; x <= kMaxQueues; x++) out.offsets[x] = (int64_t)work.size();
     out.offsets[0] = 0;
     int cur = 0;
-    for (size_t i = 0; i < work.size(); i++) {
-        out.items[i] = work[i].it;
-        int qx = queue_of[work[i].group];
+    for (size_t i = 0; i < perm.size(); i++) {
+        out.items[i] = work[perm[i]].it;
+        int qx = item_queue[perm[i]];
         while (cur < qx) out.offsets[++cur] = (int64_t)i;
     }
     while (cur < nq) out.offsets[++cur] = (int64_t)work.size();
@@ -164,6 +196,7 @@ bool view_ok(const flexsp_tensor &t)
     if (((uintptr_t)t.ptr & 15) != 0) return false;
     if (t.stride_token <= 0 || t.stride_head <= 0) return false;
     if ((t.stride_token % 8) != 0 || (t.stride_head % 8) != 0) return false;
+    if (t.stride_token > 0x3fffffff || t.stride_head > 0x3fffffff) return false;  // kernels use 32-bit strides
     return true;
 }
 
@@ -480,10 +513,10 @@ int flexsp_attn_varlen_fwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
     a.k = (const uint16_t *)k.ptr + (int64_t)kv_head_begin * k.stride_head;
     a.v = (const uint16_t *)v.ptr + (int64_t)kv_head_begin * v.stride_head;
     a.out_o = (uint16_t *)o.ptr + (int64_t)head_begin * o.stride_head;
-    a.q_st = q.stride_token; a.q_sh = q.stride_head;
-    a.k_st = k.stride_token; a.k_sh = k.stride_head;
-    a.v_st = v.stride_token; a.v_sh = v.stride_head;
-    a.o_st = o.stride_token; a.o_sh = o.stride_head;
+    a.q_st = (int32_t)q.stride_token; a.q_sh = (int32_t)q.stride_head;
+    a.k_st = (int32_t)k.stride_token; a.k_sh = (int32_t)k.stride_head;
+    a.v_st = (int32_t)v.stride_token; a.v_sh = (int32_t)v.stride_head;
+    a.o_st = (int32_t)o.stride_token; a.o_sh = (int32_t)o.stride_head;
     a.lse_out = lse;
     a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
     a.scale = scale; a.scale_l2 = scale * 1.4426950408889634f;
@@ -525,14 +558,14 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
     a.dq = (char *)dq.ptr + (int64_t)head_begin * dq.stride_head * gb;
     a.dk = (char *)dk.ptr + (int64_t)kv_head_begin * dk.stride_head * gb;
     a.dv = (char *)dv.ptr + (int64_t)kv_head_begin * dv.stride_head * gb;
-    a.q_st = q.stride_token; a.q_sh = q.stride_head;
-    a.k_st = k.stride_token; a.k_sh = k.stride_head;
-    a.v_st = v.stride_token; a.v_sh = v.stride_head;
-    a.o_st = o.stride_token; a.o_sh = o.stride_head;
-    a.do_st = dO.stride_token; a.do_sh = dO.stride_head;
-    a.dq_st = dq.stride_token; a.dq_sh = dq.stride_head;
-    a.dk_st = dk.stride_token; a.dk_sh = dk.stride_head;
-    a.dv_st = dv.stride_token; a.dv_sh = dv.stride_head;
+    a.q_st = (int32_t)q.stride_token; a.q_sh = (int32_t)q.stride_head;
+    a.k_st = (int32_t)k.stride_token; a.k_sh = (int32_t)k.stride_head;
+    a.v_st = (int32_t)v.stride_token; a.v_sh = (int32_t)v.stride_head;
+    a.o_st = (int32_t)o.stride_token; a.o_sh = (int32_t)o.stride_head;
+    a.do_st = (int32_t)dO.stride_token; a.do_sh = (int32_t)dO.stride_head;
+    a.dq_st = (int32_t)dq.stride_token; a.dq_sh = (int32_t)dq.stride_head;
+    a.dk_st = (int32_t)dk.stride_token; a.dk_sh = (int32_t)dk.stride_head;
+    a.dv_st = (int32_t)dv.stride_token; a.dv_sh = (int32_t)dv.stride_head;
     float *lse2 = plan->delta + (size_t)plan->T * plan->Hq;
     a.lse_in = lse;       // the preprocess kernel reads the caller's LSE ...
     a.lse_out = lse2;     // ... and writes it in the log2 domain next to delta

@@ -34,8 +34,9 @@ struct AttnArgs {
     void *dq, *dk, *dv;  // bf16 or fp32 elements, see grad_f32
     const float *lse_in, *delta_in;
     float *lse_out, *delta_out;
-    int64_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh;
-    int64_t dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
+    // strides in elements; 32-bit (checked by the host) to keep the kernels' scalar registers free
+    int32_t q_st, q_sh, k_st, k_sh, v_st, v_sh, o_st, o_sh, do_st, do_sh;
+    int32_t dq_st, dq_sh, dk_st, dk_sh, dv_st, dv_sh;
     int32_t T;       // tokens in the packed stream (row length of lse / delta)
     int32_t Hq;      // query heads in the subset
     int32_t G;       // query heads per kv head

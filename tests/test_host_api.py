@@ -88,12 +88,13 @@ def test_plan_covers_every_tile_once_longest_first(host_ctx, causal):
                 step = 64
             steps = [-(-c // step) for c in cost]
             assert all(a >= b for a, b in zip(steps, steps[1:]))
-            # a (sequence, head) group lives in exactly one queue
+        # a (sequence, head) group stays on one queue (one XCD, one L2) unless levelling the queues
+        # had to move some of its cheapest tiles: most groups are whole
         owner = {}
         for x in range(len(offs) - 1):
             for i in items[offs[x]:offs[x + 1]]:
-                key = (int(i["seq_start"]), int(i["head"]))
-                assert owner.setdefault(key, x) == x
+                owner.setdefault((int(i["seq_start"]), int(i["head"])), set()).add(x)
+        assert sum(1 for v in owner.values() if len(v) == 1) >= 0.6 * len(owner)
     assert plan.workspace_bytes == 2 * sum(lens) * hq * 4      # delta and log2-domain LSE
     plan.close()
 
@@ -108,10 +109,25 @@ def test_plan_balances_queues_on_the_long_tail_config(host_ctx):
     for x in range(8):
         seg = items[offs[x]:offs[x + 1]]
         load.append(sum(-(-min(int(i["seq_len"]), (int(i["tile"]) + 1) * rows) // 64) for i in seg))
-    assert max(load) <= 1.05 * (sum(load) / 8)
+    assert max(load) <= 1.01 * (sum(load) / 8) + 2
     # the very first item of each queue is one of the longest tiles of the batch
     longest = max(lens)
     assert all(int(items[offs[x]]["seq_len"]) >= 0.2 * longest for x in range(8))
+    plan.close()
+
+
+def test_plan_levels_queues_when_one_sequence_dominates(host_ctx):
+    """Config 1: one sequence holds 60 % of the work and there are only 4 heads, so whole
+    (sequence, head) groups cannot balance 8 queues; tiles must be moved."""
+    cfg = wl.CONFIGS[1]
+    lens = wl.lengths(cfg)
+    plan = fx.Plan(host_ctx, wl.cu_seqlens(lens), cfg.hq, cfg.hkv, cfg.d, True)
+    for which, step in ((fx.PASS_FWD, 64), (fx.PASS_BWD_DQ, 64)):
+        items, offs = plan.items(which)
+        rows = plan.tile_rows(which)
+        load = [sum(-(-min(int(i["seq_len"]), (int(i["tile"]) + 1) * rows) // step) for i in items[offs[x]:offs[x + 1]])
+                for x in range(8)]
+        assert max(load) - min(load) <= max(-(-max(lens) // step), 4), load
     plan.close()
 
 

@@ -37,6 +37,37 @@ BF16_MFMA_PEAK = 2.5e15     # MI355X dense bf16 MFMA, FLOP/s (256 CU x 4 SIMD x 
 HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 
 
+def permute_leg(ctx, fx, wl, torch, stream):
+    """Achieved HBM bandwidth of pack / unpack on the [32768, 32, 128] bf16, P = 8 shape, rotating
+    over 4 distinct buffer pairs (2 GiB) so the 256 MB last-level cache cannot serve the reads;
+    then the same kernel with P = 1, which is a plain copy: the ceiling this permute can reach."""
+    c1 = wl.CONFIGS[1]
+    Tp, Hp_tot, Pp, D = c1.tokens, c1.hq * c1.sp_degree, c1.sp_degree, c1.d
+    nbuf = 4
+    dev = "cuda"
+    srcs = [torch.randn((Tp, Hp_tot, D), device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(nbuf)]
+    dsts = [torch.empty((Pp, Tp, Hp_tot // Pp, D), dtype=torch.bfloat16, device=dev) for _ in range(nbuf)]
+    nbytes = 2 * Tp * Hp_tot * D * 2
+    res = {}
+
+    def timed(name, key, run):
+        for i in range(10):
+            run(i)
+        ctx.profile_start(64)
+        for i in range(40):
+            run(i)
+        ms, n = ctx.profile_stop()[key]
+        res[name] = {"avg_ms": ms / n, "GBps": nbytes / (ms / n * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": nbytes / (ms / n * 1e-3) / HBM_PEAK}
+
+    timed("pack", "pack", lambda i: fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf], Pp, stream))
+    timed("unpack", "unpack", lambda i: fx.flexsp_unpack(ctx, dsts[i % nbuf], srcs[i % nbuf], stream))
+    timed("plain_copy_same_kernel", "pack",
+          lambda i: fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf].view(1, Tp, Hp_tot, D), 1, stream))
+    return {"shape": [Tp, Hp_tot, D], "sp_degree": Pp, "dtype": "bf16", "bytes_per_call": nbytes,
+            "buffers_rotated": nbuf, "peak_GBps": HBM_PEAK / 1e9, **res}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +78,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-permute-leg", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="step = plan + fwd + bwd (no permutes)")
+    ap.add_argument("--permute-only", action="store_true",
+                    help="only the permute bandwidth leg: 50 pack, 50 unpack, 50 plain copies (pack with P = 1), "
+                         "in that order (for counter collection)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives are part of it); use --gpus 1",
@@ -57,6 +91,12 @@ def main() -> int:
     import torch
     from paper_2412_01523_amd import binding as fx
     from paper_2412_01523_amd import workloads as wl
+
+    if args.permute_only:
+        torch.cuda.set_device(0)
+        ctx = fx.Context(0)
+        print(json.dumps({"permute": permute_leg(ctx, fx, wl, torch, torch.cuda.current_stream())}))
+        return 0
 
     cfg = next(c for c in wl.CONFIGS if c.name == args.workload)
     lens = wl.lengths(cfg)
@@ -164,46 +204,8 @@ def main() -> int:
         "roofline": roofline,
     }
 
-    # ---- permute leg: achieved HBM bandwidth on the [32768, 32, 128] bf16, P = 8 shape, rotating
-    # over 4 distinct buffer pairs (2 GiB) so the 256 MB last-level cache cannot serve the reads
     if not args.no_permute_leg:
-        c1 = wl.CONFIGS[1]
-        Tp, Hp_tot, Pp = c1.tokens, c1.hq * c1.sp_degree, c1.sp_degree
-        nbuf = 4
-        srcs = [torch.randn((Tp, Hp_tot, c1.d), device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(nbuf)]
-        dsts = [torch.empty((Pp, Tp, Hp_tot // Pp, c1.d), dtype=torch.bfloat16, device=dev) for _ in range(nbuf)]
-        res = {}
-        for which in ("pack", "unpack"):
-            def run(i):
-                if which == "pack":
-                    fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf], Pp, stream)
-                else:
-                    fx.flexsp_unpack(ctx, dsts[i % nbuf], srcs[i % nbuf], stream)
-            for i in range(10):
-                run(i)
-            ctx.profile_start(64)
-            for i in range(40):
-                run(i)
-            pr = ctx.profile_stop()
-            ms, n = pr[which]
-            nbytes = 2 * Tp * Hp_tot * c1.d * 2
-            res[which] = {"avg_ms": ms / n, "GBps": nbytes / (ms / n * 1e-3) / 1e9,
-                          "frac_of_hbm_peak": nbytes / (ms / n * 1e-3) / HBM_PEAK}
-        # the same kernel with P = 1 is a plain copy: the ceiling this permute can reach
-        one = dsts[0].view(1, Tp, Hp_tot, c1.d)
-        for i in range(10):
-            fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf].view(1, Tp, Hp_tot, c1.d), 1, stream)
-        ctx.profile_start(64)
-        for i in range(40):
-            fx.flexsp_pack(ctx, srcs[i % nbuf], dsts[i % nbuf].view(1, Tp, Hp_tot, c1.d), 1, stream)
-        pr = ctx.profile_stop()
-        ms, n = pr["pack"]
-        res["plain_copy_same_kernel"] = {"avg_ms": ms / n, "GBps": 2 * Tp * Hp_tot * c1.d * 2 / (ms / n * 1e-3) / 1e9}
-        del one
-        out["permute"] = {"shape": [Tp, Hp_tot, c1.d], "sp_degree": Pp, "dtype": "bf16",
-                          "bytes_per_call": 2 * Tp * Hp_tot * c1.d * 2, "buffers_rotated": nbuf,
-                          "peak_GBps": HBM_PEAK / 1e9, **res}
-        del srcs, dsts
+        out["permute"] = permute_leg(ctx, fx, wl, torch, stream)
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     if not args.no_cpu_baseline:

@@ -68,6 +68,67 @@ def permute_leg(ctx, fx, wl, torch, stream):
             "buffers_rotated": nbuf, "peak_GBps": HBM_PEAK / 1e9, **res}
 
 
+def cost_model_leg(ctx, fx, wl, torch, np):
+    """Paper Sec. 4.1.2, Eq. 12: T_comp = alpha1*sum(s^2) + alpha2*sum(s) + beta1, coefficients
+    "obtained through profiling".  Profiles attention fwd+bwd (8 heads, D = 128, causal) on 24 seeded
+    synthetic batches of different sizes and length mixes, fits on the even-numbered ones, and
+    reports the relative error on every batch (the paper reports < 6 %)."""
+    from paper_2412_01523_amd import cost_model as cm
+    H, D = 8, 128
+    rng = np.random.Generator(np.random.Philox(key=[wl.BASE_SEED, 4242]))
+
+    def fill(draw, total):
+        out, left = [], total
+        while left > 0:
+            s = min(int(draw()), left)
+            out.append(s)
+            left -= s
+        return out
+
+    batches = []
+    for total in (16384, 32768, 65536, 131072):
+        batches.append(fill(lambda: np.clip(np.rint(np.exp(rng.normal(7.0, 1.2))), 128, 32768), total))
+        batches.append(fill(lambda: np.clip(np.floor(256.0 * (1.0 - rng.random()) ** (-1 / 1.1)), 256, 65536), total))
+        batches.append(fill(lambda: rng.integers(64, 1025), total))
+        batches.append(fill(lambda: rng.integers(2048, 8193), total))
+        batches.append([total // 4] * 4)
+        batches.append([total])
+    times = []
+    for lens in batches:
+        cu = wl.cu_seqlens(lens)
+        T = int(cu[-1])
+        q = torch.randn((T, H, D), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        k, v, g = torch.randn_like(q), torch.randn_like(q), torch.randn_like(q)
+        o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        lse = torch.empty((H, T), dtype=torch.float32, device="cuda")
+        cud = torch.from_numpy(cu).cuda()
+        plan = fx.Plan(ctx, cu, H, H, D, True)
+
+        def once():
+            fx.flexsp_attn_varlen_fwd(ctx, plan, q, k, v, cud, o, lse)
+            fx.flexsp_attn_varlen_bwd(ctx, plan, q, k, v, o, g, lse, cud, dq, dk, dv)
+
+        once(); once()
+        reps = []
+        for _ in range(5):
+            ctx.profile_start(8)
+            once()
+            pr = ctx.profile_stop()
+            reps.append(sum(pr[kk][0] for kk in ("fwd", "bwd_delta", "bwd_dkv", "bwd_dq")))
+        times.append(float(np.median(reps)))
+        plan.close()
+        del q, k, v, g, o, dq, dk, dv, lse
+    coef = cm.fit(batches[0::2], times[0::2])
+    err = cm.relative_errors(coef, batches, times)
+    return {"alpha1_ms_per_token2": coef[0], "alpha2_ms_per_token": coef[1], "beta1_ms": coef[2],
+            "heads": H, "head_dim": D, "batches": len(batches), "fitted_on": len(batches[0::2]),
+            "max_abs_rel_error_fitted": float(np.abs(err[0::2]).max()),
+            "max_abs_rel_error_held_out": float(np.abs(err[1::2]).max()),
+            "mean_abs_rel_error": float(np.abs(err).mean()),
+            "per_batch": [{"tokens": int(sum(b)), "sequences": len(b), "max_len": int(max(b)), "ms": t,
+                           "rel_error": float(e)} for b, t, e in zip(batches, times, err)]}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +139,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-permute-leg", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="step = plan + fwd + bwd (no permutes)")
+    ap.add_argument("--cost-model", action="store_true",
+                    help="only the cost-model leg: time attention fwd+bwd on 24 synthetic batches, fit the "
+                         "paper's alpha-beta computation model (Eq. 12) on half of them, report the error on all")
     ap.add_argument("--permute-only", action="store_true",
                     help="only the permute bandwidth leg: 50 pack, 50 unpack, 50 plain copies (pack with P = 1), "
                          "in that order (for counter collection)")
@@ -91,6 +155,12 @@ def main() -> int:
     import torch
     from paper_2412_01523_amd import binding as fx
     from paper_2412_01523_amd import workloads as wl
+
+    if args.cost_model:
+        torch.cuda.set_device(0)
+        ctx = fx.Context(0)
+        print(json.dumps({"cost_model": cost_model_leg(ctx, fx, wl, torch, np)}))
+        return 0
 
     if args.permute_only:
         torch.cuda.set_device(0)

@@ -53,44 +53,33 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const AttnArgs a)
 // ------------------------------------------------------------------------------ dK / dV
 // One work item = 64 keys of one (sequence, kv head).  The accumulators of 32 keys x D for both
 // dK and dV, next to the K and V fragments, would take more than half of the register file and
-// leave one wavefront per SIMD with nothing to overlap its exponentials with.  So TWO wavefronts
+// leave one wavefront per SIMD with nothing to hide its LDS latencies behind.  So TWO wavefronts
 // share each block of 32 keys: per step of 64 query rows, wavefront j of the pair computes
-// S = Q K^T, dP = dO V^T, P and dS for query block j only, the pair swaps the bf16 P / dS
-// fragments through LDS (a fragment is written and read back by the same lane numbers, so the
-// swap is a plain linear copy), and then each wavefront accumulates dV^T += dO^T P and
-// dK^T += Q^T dS for BOTH query blocks but only for its own half of the head dim.  No matrix
-// work is duplicated, every wavefront fits in 256 registers, and two workgroups share a CU.
+// S = Q K^T, dP = dO V^T, P and dS for query block j only; then wavefront 0 accumulates
+// dV^T += dO^T P and wavefront 1 accumulates dK^T += Q^T dS, each over BOTH query blocks.  For
+// the other block each needs one bf16 fragment set from its partner (P one way, dS the other),
+// swapped through LDS: a fragment is written and read back by the same lane numbers, so the swap
+// is a plain linear copy.  No matrix work is duplicated, every wavefront fits in 256 registers,
+// and two workgroups share a CU.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArgs a)
 {
     typedef LdsTile<D> L;
-    typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
     constexpr int KS = D / 16;
-    constexpr int DBH = D / 64;                 // 32-wide head-dim blocks per wavefront
+    constexpr int DB = D / 32;
     constexpr int BQ = kDkvBq;                  // query rows per step: two 32-row blocks
     constexpr int QTILE = BQ * L::ROWB;
-    constexpr int STEP = 2 * QTILE;             // Q | dO
-    constexpr int XSLOT = 4096;                 // P (2 KB) and dS (2 KB) of one 32 x 32 block
-    // [buffer][Q | dO] then 4 exchange slots
+    constexpr int STEP = 2 * QTILE + 512;       // Q | dO | lse2[64] delta[64]
+    constexpr int XSLOT = 2048;                 // one 32 x 32 bf16 block (P or dS)
     __shared__ __attribute__((aligned(1024))) char smem[2 * STEP + 4 * XSLOT];
     char *const exch = smem + 2 * STEP;
 
     const int tid = threadIdx.x;
     const int lane0 = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kb = wave >> 1, j = wave & 1;     // key block, role inside the pair
-    int nat[KS];                                // natural-read offsets, as in LaneOffsets
-    int trw[DBH][2];                            // transpose-read offsets of this wavefront's head-dim blocks
-    {
-        LaneOffsets<D> lo;
-        lo.init(lane0);
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) nat[ks] = lo.nat[ks];
-#pragma unroll
-        for (int d = 0; d < DBH; d++)
-#pragma unroll
-            for (int h = 0; h < 2; h++) trw[d][h] = j ? lo.tr[DBH + d][h] : lo.tr[d][h];
-    }
+    const int kb = wave >> 1, j = wave & 1;     // key block; role: 0 accumulates dV, 1 accumulates dK
+    LaneOffsets<D> lo;
+    lo.init(lane0);
     ItemDealer deal;
     deal.init(a.pq);
 
@@ -125,6 +114,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 load_tile_async<D, BQ>(base, qb, a.q_st, qs, s - 1, wave, lane);
                 load_tile_async<D, BQ>(base + QTILE, gb, a.do_st, qs, s - 1, wave, lane);
             }
+            if (wave < 2) {  // wavefront 0: lse2 of the 64 rows, wavefront 1: delta
+                const float *src = (wave ? a.delta_in : a.lse_in) + (int64_t)h * a.T + tok0 + min(qs + lane, s - 1);
+                global_to_lds4(src, base + 2 * QTILE + wave * 256);
+            }
         };
         if (total > 0) prefetch(0, 0);
 
@@ -143,17 +136,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 vf[ks] = f.v;
             }
         }
-        f32x16 dkT[DBH], dvT[DBH];  // rows = this wavefront's half of the head dim, column = key
+        f32x16 accT[DB];  // dV^T (role 0) or dK^T (role 1): rows = head dim, column = key
 #pragma unroll
-        for (int d = 0; d < DBH; d++)
+        for (int d = 0; d < DB; d++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) dkT[d][i] = dvT[d][i] = 0.f;
+            for (int i = 0; i < 16; i++) accT[d][i] = 0.f;
 
         auto step_fn = [&](auto bufc, int step) {
             constexpr int BUF = decltype(bufc)::value;
             const char *sQ = smem + BUF * STEP;
             const char *sG = sQ + QTILE;
-            const int h = g * a.G + step / nsteps;
+            const float *sL = (const float *)(sQ + 2 * QTILE);  // lse2[64], delta[64]
             const int q_lo = qfirst + (step % nsteps) * BQ;
             // a block (32 queries x the pair's 32 keys) is empty when it lies past the end of the
             // sequence or wholly above the diagonal; both wavefronts of a pair agree on that
@@ -161,13 +154,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 const int lo_ = q_lo + qb * 32;
                 return lo_ >= s || (a.causal && lo_ + 31 < wk_lo);
             };
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++) asm volatile("" : "+v"(nat[ks]));  // see LaneOffsets::pin
-#pragma unroll
-            for (int d = 0; d < DBH; d++) {
-                asm volatile("" : "+v"(trw[d][0]));
-                asm volatile("" : "+v"(trw[d][1]));
-            }
+            lo.pin();
             wait_vmem();
             __syncthreads();  // tile `step` is in LDS; the previous step's exchange slots are free
             if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
@@ -176,38 +163,31 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             uint32_t pp[8], dd[8];
             const int my_lo = q_lo + j * 32;
             if (!empty(j)) {
-                // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e.  (Rows past the end of the
-                // sequence read neighbouring scratch values; they are masked below.)
-                const float *lp = a.lse_in + (int64_t)h * a.T + tok0 + my_lo + 4 * hl;
-                const float *dp = a.delta_in + (int64_t)h * a.T + tok0 + my_lo + 4 * hl;
-                f32x4 l4[4], d4[4];
-#pragma unroll
-                for (int i4 = 0; i4 < 4; i4++) {
-                    l4[i4] = *(const f32x4u *)(lp + 8 * i4);
-                    d4[i4] = *(const f32x4u *)(dp + 8 * i4);
-                }
                 f32x16 sacc, pacc;
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ks++) {
-                    sacc = mfma32(lds_nat(sQ, j * 32 * L::ROWB + nat[ks]), kf[ks], sacc);
-                    pacc = mfma32(lds_nat(sG, j * 32 * L::ROWB + nat[ks]), vf[ks], pacc);
+                    sacc = mfma32(lds_nat(sQ, j * 32 * L::ROWB + lo.nat[ks]), kf[ks], sacc);
+                    pacc = mfma32(lds_nat(sG, j * 32 * L::ROWB + lo.nat[ks]), vf[ks], pacc);
                 }
+                // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e
                 const bool masked = (a.causal && my_lo < wk_lo + 31) || (my_lo + 32 > s);
                 auto probs = [&](auto maskc) {
                     constexpr bool MASK = decltype(maskc)::value;
 #pragma unroll
                     for (int i4 = 0; i4 < 4; i4++) {
+                        const f32x4 l4 = *(const f32x4 *)(sL + j * 32 + 8 * i4 + 4 * hl);
+                        const f32x4 d4 = *(const f32x4 *)(sL + 64 + j * 32 + 8 * i4 + 4 * hl);
                         float p[4], ds[4];
 #pragma unroll
                         for (int e = 0; e < 4; e++) {
-                            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * i4 + e], a.scale_l2, -l4[i4][e]));
+                            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * i4 + e], a.scale_l2, -l4[e]));
                             if (MASK) {
                                 const int qr = my_lo + 8 * i4 + 4 * hl + e;
                                 p[e] = ((a.causal && qr < kvrow) || qr >= s) ? 0.f : p[e];
                             }
-                            ds[e] = p[e] * (pacc[4 * i4 + e] - d4[i4][e]);
+                            ds[e] = p[e] * (pacc[4 * i4 + e] - d4[e]);
                         }
                         pp[2 * i4] = pack_bf16x2(p[0], p[1]);
                         pp[2 * i4 + 1] = pack_bf16x2(p[2], p[3]);
@@ -219,30 +199,33 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                     probs(std::true_type{});
                 else
                     probs(std::false_type{});
+                // hand the partner what it accumulates: role 0 gives dS, role 1 gives P
                 char *slot = exch + (kb * 2 + j) * XSLOT + lane * 16;
-                *(u32x4 *)(slot) = u32x4{pp[0], pp[1], pp[2], pp[3]};
-                *(u32x4 *)(slot + 1024) = u32x4{pp[4], pp[5], pp[6], pp[7]};
-                *(u32x4 *)(slot + 2048) = u32x4{dd[0], dd[1], dd[2], dd[3]};
-                *(u32x4 *)(slot + 3072) = u32x4{dd[4], dd[5], dd[6], dd[7]};
+                *(u32x4 *)(slot) = j ? u32x4{pp[0], pp[1], pp[2], pp[3]} : u32x4{dd[0], dd[1], dd[2], dd[3]};
+                *(u32x4 *)(slot + 1024) = j ? u32x4{pp[4], pp[5], pp[6], pp[7]} : u32x4{dd[4], dd[5], dd[6], dd[7]};
             }
             __syncthreads();  // the partner's fragments are visible
 
-            // ---- phase 2: accumulate both query blocks into this wavefront's half of the head dim
+            // ---- phase 2: role 0: dV^T += dO^T P, role 1: dK^T += Q^T dS, both query blocks
+            const char *sX = j ? sQ : sG;
 #pragma unroll
             for (int qb = 0; qb < 2; qb++) {
                 if (empty(qb)) continue;
-                const char *slot = exch + (kb * 2 + qb) * XSLOT + lane * 16;
+                Frag8 f[2];
+                if (qb == j) {  // this wavefront's own block: from registers
+                    f[0].u = j ? u32x4{dd[0], dd[1], dd[2], dd[3]} : u32x4{pp[0], pp[1], pp[2], pp[3]};
+                    f[1].u = j ? u32x4{dd[4], dd[5], dd[6], dd[7]} : u32x4{pp[4], pp[5], pp[6], pp[7]};
+                } else {        // the partner's block: from its slot
+                    const char *slot = exch + (kb * 2 + qb) * XSLOT + lane * 16;
+                    f[0].u = *(const u32x4 *)(slot);
+                    f[1].u = *(const u32x4 *)(slot + 1024);
+                }
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++) {
-                    Frag8 pf, df;
-                    pf.u = *(const u32x4 *)(slot + hf * 1024);
-                    df.u = *(const u32x4 *)(slot + 2048 + hf * 1024);
                     const int rowoff = (qb * 32 + hf * 16) * L::ROWB;
 #pragma unroll
-                    for (int d = 0; d < DBH; d++) {
-                        dvT[d] = mfma32(lds_tr(sG, rowoff + trw[d][0], rowoff + trw[d][1]), pf.v, dvT[d]);
-                        dkT[d] = mfma32(lds_tr(sQ, rowoff + trw[d][0], rowoff + trw[d][1]), df.v, dkT[d]);
-                    }
+                    for (int d = 0; d < DB; d++)
+                        accT[d] = mfma32(lds_tr(sX, rowoff + lo.tr[d][0], rowoff + lo.tr[d][1]), f[hf].v, accT[d]);
                 }
             }
         };
@@ -251,23 +234,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             if (step + 1 < total) step_fn(std::integral_constant<int, 1>{}, step + 1);
         }
 
-        const int64_t d0 = j * (D / 2);  // first head-dim element of this wavefront's half
+        // role 0 writes dV rows, role 1 writes dK rows (scaled)
+        char *const out = (char *)(j ? a.dk : a.dv);
+        const int64_t ost = j ? a.dk_st : a.dv_st, osh = j ? a.dk_sh : a.dv_sh;
+        const float mul = j ? a.scale : 1.0f;
         if (a.grad_f32) {
-            if (kvrow < s) {
-                store_rowT<DBH>((char *)a.dk + ((tok0 + kvrow) * a.dk_st + (int64_t)g * a.dk_sh + d0) * 4, true, dkT,
-                                a.scale, hl);
-                store_rowT<DBH>((char *)a.dv + ((tok0 + kvrow) * a.dv_st + (int64_t)g * a.dv_sh + d0) * 4, true, dvT,
-                                1.0f, hl);
-            }
+            if (kvrow < s) store_rowT<DB>(out + ((tok0 + kvrow) * ost + (int64_t)g * osh) * 4, true, accT, mul, hl);
         } else if (wk_lo < s) {
-            // through the Q/dO buffer the last step did not use: 2 x 32 half-rows per wavefront
-            char *stage = smem + (total & 1) * STEP + wave * (2 * 32 * (D / 2) * 2);
-            const int nrows = min(32, s - wk_lo);
-            store_rowT_bf16_lds<DBH>(stage, (uint16_t *)a.dk + (tok0 + wk_lo) * a.dk_st + (int64_t)g * a.dk_sh + d0,
-                                     a.dk_st, nrows, dkT, a.scale, lane);
-            store_rowT_bf16_lds<DBH>(stage + 32 * (D / 2) * 2,
-                                     (uint16_t *)a.dv + (tok0 + wk_lo) * a.dv_st + (int64_t)g * a.dv_sh + d0, a.dv_st,
-                                     nrows, dvT, 1.0f, lane);
+            // through the Q/dO buffer the last step did not use (every wavefront is past its barriers)
+            store_rowT_bf16_lds<DB>(smem + (total & 1) * STEP + wave * (32 * L::ROWB),
+                                    (uint16_t *)out + (tok0 + wk_lo) * ost + (int64_t)g * osh, ost,
+                                    min(32, s - wk_lo), accT, mul, lane);
         }
         barrier_lds_only();  // the tiles and the exchange slots are reused by the next item
     }

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
     deal.init(a.pq);
 
     for (int item = deal.next(); item >= 0; item = deal.next()) {
-        const flexsp_item it = a.pq.items[item];
+        const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
         int lane = lane0;
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
     deal.init(a.pq);
 
     for (int item = deal.next(); item >= 0; item = deal.next()) {
-        const flexsp_item it = a.pq.items[item];
+        const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
         int lane = lane0;

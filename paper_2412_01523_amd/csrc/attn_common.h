@@ -291,6 +291,22 @@ __device__ __forceinline__ void store_rowT_bf16_lds(char *stage, uint16_t *g, in
     }
 }
 
+// Descriptor of item `idx` as wave-uniform (scalar) values.  The index is uniform, but the load
+// itself is a vector load (the compiler cannot rule out that the kernel's own stores clobber the
+// list), so without the readfirstlane every quantity derived from the descriptor - sequence
+// length, tile bounds, loop trip counts, base addresses - would live in vector registers and
+// every branch on them would be compiled as a divergent one.
+__device__ __forceinline__ flexsp_item load_item(const flexsp_item *items, int idx)
+{
+    const flexsp_item v = items[idx];
+    flexsp_item it;
+    it.seq_start = __builtin_amdgcn_readfirstlane(v.seq_start);
+    it.seq_len = __builtin_amdgcn_readfirstlane(v.seq_len);
+    it.tile = __builtin_amdgcn_readfirstlane(v.tile);
+    it.head = __builtin_amdgcn_readfirstlane(v.head);
+    return it;
+}
+
 // Work distribution.  The plan holds one longest-first item list per XCD, balanced on the host.
 // Workgroup w runs on XCD w % nq (workgroups are dispatched round-robin over the XCDs) and is
 // the (w / nq)-th of the W = gridDim / nq workgroups there.  The list is dealt to those W

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     deal.init(a.pq);
 
     for (int item = deal.next(); item >= 0; item = deal.next()) {
-        const flexsp_item it = a.pq.items[item];
+        const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
         int lane = lane0;

@@ -134,7 +134,8 @@ int flexsp_unpack(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_
 /*
  * Strided view of a [T, heads, D] bf16 tensor in device memory: element (t, h, d) lives at
  * ptr + (t*stride_token + h*stride_head + d) elements.  The last dim is contiguous, ptr and
- * both strides (in elements) must keep every row 16-byte aligned (multiples of 8 elements).
+ * both strides (in elements) must keep every row 16-byte aligned (multiples of 8 elements);
+ * stride_token <= 2^24 and stride_head < 2^30, else FLEXSP_INVALID_ARGUMENT.
  * A view lets a heads subset of a larger tensor be used in place.
  */
 typedef struct flexsp_tensor {

@@ -30,6 +30,15 @@ FLAGS = [
 ]
 
 
+# The attention kernels lay out their instruction order by hand (LDS reads issued several matrix
+# instructions ahead of their use, softmax arithmetic placed between matrix instructions).  Both
+# of the compiler's pre-allocation schedulers otherwise sink every LDS read to just before its
+# use, which exposes the full LDS latency once per matrix instruction; with them off the order
+# of the source is the order of the code.
+SOURCE_ORDER = ["-mllvm", "-pre-RA-sched=source", "-mllvm", "-enable-misched=false"]
+PER_SOURCE = {"attn_fwd.hip": SOURCE_ORDER}
+
+
 def _hipcc() -> str:
     for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if c and (os.path.isabs(c) and os.path.exists(c) or not os.path.isabs(c)):
@@ -48,7 +57,7 @@ def _compile(src: str, force: bool, extra) -> Path:
     if (not force and o.exists() and o.stat().st_mtime > s.stat().st_mtime
             and o.stat().st_mtime > _newest_header()):
         return o
-    cmd = [_hipcc(), *FLAGS, *extra, "-c", str(s), "-o", str(o)]
+    cmd = [_hipcc(), *FLAGS, *PER_SOURCE.get(src, []), *extra, "-c", str(s), "-o", str(o)]
     r = subprocess.run(cmd, capture_output=True, text=True)
     # hipcc's host pass does not know the packed-fp32 feature and says so: harmless
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)

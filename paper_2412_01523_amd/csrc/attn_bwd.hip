@@ -80,10 +80,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
     const int kb = wave >> 1, j = wave & 1;     // key block; role: 0 accumulates dV, 1 accumulates dK
     LaneOffsets<D> lo;
     lo.init(lane0);
+    __shared__ int deal_word;
     ItemDealer deal;
-    deal.init(a.pq);
 
-    for (int item = deal.next(); item >= 0; item = deal.next()) {
+    for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
+        deal.prefetch();
         const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
@@ -246,8 +247,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                                     (uint16_t *)out + (tok0 + wk_lo) * ost + (int64_t)g * osh, ost,
                                     min(32, s - wk_lo), accT, mul, lane);
         }
-        barrier_lds_only();  // the tiles and the exchange slots are reused by the next item
+        // deal.advance() holds the barrier after which the tiles and the exchange slots are reused
     }
+    deal.finish();
 }
 
 // ------------------------------------------------------------------------------ dQ
@@ -265,10 +267,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     LaneOffsets<D> lo;
     lo.init(lane0);
+    __shared__ int deal_word;
     ItemDealer deal;
-    deal.init(a.pq);
 
-    for (int item = deal.next(); item >= 0; item = deal.next()) {
+    for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
+        deal.prefetch();
         const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
@@ -392,8 +395,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                                     (uint16_t *)a.dq + (tok0 + wq_lo) * a.dq_st + (int64_t)h * a.dq_sh, a.dq_st,
                                     min(32, s - wq_lo), dqT, a.scale, lane);
         }
-        barrier_lds_only();  // the LDS buffers are reused by the next item
+        // deal.advance() holds the barrier after which the LDS buffers are reused by the next item
     }
+    deal.finish();
 }
 
 }  // namespace

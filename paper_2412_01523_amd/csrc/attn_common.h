@@ -81,13 +81,29 @@ typedef __attribute__((address_space(1))) const void glb_void_t;
 
 // 16 bytes per lane straight from global memory into LDS: lane l's data lands at lds + 16*l.
 // `lds` must be wave-uniform.  Completion is tracked by vmcnt.
+// Issued as inline assembly on purpose: when the compiler knows that a copy into LDS is in
+// flight it makes every later LDS read wait for ALL outstanding copies (it cannot tell that
+// the copy fills the other buffer), which would stall each tile step on the prefetch of the
+// next tile.  The one real dependency, tile t landed before step t reads it, is the explicit
+// wait_vmem() + barrier at the top of a step.
 __device__ __forceinline__ void global_to_lds16(const void *g, void *lds)
 {
-    __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds, 16, 0, 0);
+    const uint32_t dst = (uint32_t)(uintptr_t)lds;  // low half of a generic LDS pointer = LDS byte address
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst) : "memory");
+}
+// The same with the address split into a wave-uniform 64-bit base (scalar registers) and a
+// 32-bit per-lane byte offset: the per-lane part of a tile copy is then one register for the
+// whole kernel instead of one 64-bit address per copy instruction.
+__device__ __forceinline__ void global_to_lds16(const void *base, uint32_t lane_off, void *lds)
+{
+    const uint32_t dst = (uint32_t)(uintptr_t)lds;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(dst)
+                 : "memory");
 }
 __device__ __forceinline__ void global_to_lds4(const void *g, void *lds)
 {
-    __builtin_amdgcn_global_load_lds((glb_void_t *)g, (lds_void_t *)(uintptr_t)lds, 4, 0, 0);
+    const uint32_t dst = (uint32_t)(uintptr_t)lds;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(dst) : "memory");
 }
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0)
 
@@ -140,8 +156,20 @@ __device__ __forceinline__ void load_tile_async_fast(char *tile, const uint16_t 
     static_assert((kThreads / L::CH) % 16 == 0, "rows per pass must be a multiple of the swizzle period");
 #pragma unroll
     for (int n = 0; n < ROWS * L::CH / kThreads; n++)
-        global_to_lds16((const char *)(g_tile + (int64_t)n * (kThreads / L::CH) * stride) + goff,
-                        tile + (n * kThreads + wave * 64) * 16);
+        global_to_lds16(g_tile + (int64_t)n * (kThreads / L::CH) * stride, goff, tile + (n * kThreads + wave * 64) * 16);
+}
+
+// One of the ROWS*CH/kThreads copy instructions of load_tile_async_fast (n is a compile-time
+// constant at every call site).  Lets a kernel place the copies of the next tile one by one
+// between its matrix instructions: issued back to back by all wavefronts right after the
+// barrier they queue up behind the 64 bytes per cycle a compute unit's load path delivers, and
+// every wavefront stalls until its own have been accepted.
+template <int D>
+__device__ __forceinline__ void load_tile_async_fast_one(char *tile, const uint16_t *g_tile, int32_t stride,
+                                                         uint32_t goff, int wave, int n)
+{
+    typedef LdsTile<D> L;
+    global_to_lds16(g_tile + (int64_t)n * (kThreads / L::CH) * stride, goff, tile + (n * kThreads + wave * 64) * 16);
 }
 
 // Per-lane byte offsets of operand fragments inside a tile (computed once per kernel).
@@ -308,29 +336,96 @@ __device__ __forceinline__ flexsp_item load_item(const flexsp_item *items, int i
 }
 
 // Work distribution.  The plan holds one longest-first item list per XCD, balanced on the host.
-// Workgroup w runs on XCD w % nq (workgroups are dispatched round-robin over the XCDs) and is
-// the (w / nq)-th of the W = gridDim / nq workgroups there.  The list is dealt to those W
-// workgroups in snake order (round 0: 0..W-1, round 1: W-1..0, ...), which is longest-processing-
-// time-first scheduling done ahead of time: every workgroup knows its items without touching a
-// shared counter (fetching through one atomic per item made 64 workgroups queue up on the same
-// address at every item boundary), and can fetch the next descriptor while it works.
+// Workgroup w runs on XCD w % nq (workgroups are dispatched round-robin over the XCDs); that
+// list is its home queue, and it is the (w / nq)-th of the W workgroups there.  Items are handed
+// out as tickets: ticket l < W is workgroup l's first item (no memory access), tickets from W on
+// come from one atomic counter per queue, longest item first, so the list is scheduled
+// longest-processing-time-first against the run times as they really turn out.  The ticket for
+// the NEXT item is drawn when an item starts (prefetch), so the counter's round trip (a few
+// microseconds when 64 workgroups hit the same address) is hidden behind the item's work.  A
+// workgroup whose home queue is empty goes on to the other XCDs' queues, one after the other,
+// and only stops when all are empty: the tail of the launch is spread over the whole chip.
+// Only wavefront 0 talks to the counters; the item index reaches the others through one LDS
+// word and the barrier that ends an item anyway.  The last workgroup to leave zeroes the
+// counters, so a launch (or a graph replay of it) always finds them clear; launches that share
+// a plan's counters must not overlap.
 struct ItemDealer {
-    int begin, end, W, l, round;
-    __device__ __forceinline__ void init(const PassQueues &pq)
+    const int32_t *offsets;
+    int32_t *counters;  // [nq] tickets drawn beyond the static ones, [nq] = workgroups that left
+    int *slot;          // LDS word
+    int nq, q, hops, wave, lane;
+    int pending;        // wavefront 0, lane 0: ticket drawn ahead (offset from W of queue q)
+
+    __device__ __forceinline__ int wgs_of(int qq) const { return ((int)gridDim.x - qq + nq - 1) / nq; }
+    __device__ __forceinline__ int draw(int qq)  // wavefront 0 only; waits for the answer
     {
-        const int x = (int)(blockIdx.x % pq.nq);
-        W = (int)(gridDim.x / pq.nq);
-        l = (int)(blockIdx.x / pq.nq);
-        begin = pq.offsets[x];
-        end = pq.offsets[x + 1];
-        round = 0;
+        int tk = 0;
+        if (lane == 0) tk = atomicAdd(counters + qq, 1);
+        return __builtin_amdgcn_readfirstlane(tk);
     }
-    // index of this workgroup's next item, or -1 when its share is done
-    __device__ __forceinline__ int next()
+    // wavefront 0: first item of the other queues, in ring order, or -1 when all are empty
+    __device__ __forceinline__ int steal()
     {
-        const int idx = begin + round * W + ((round & 1) ? (W - 1 - l) : l);
-        round++;
-        return idx < end ? idx : -1;
+        while (hops < nq - 1) {
+            hops++;
+            q = q + 1 == nq ? 0 : q + 1;
+            const int idx = offsets[q] + wgs_of(q) + draw(q);
+            if (idx < offsets[q + 1]) return idx;
+        }
+        return -1;
+    }
+    // hands wavefront 0's `idx` to the whole workgroup; contains the barrier that separates items
+    __device__ __forceinline__ int publish(int idx)
+    {
+        if (wave == 0 && lane == 0) *slot = idx;
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the LDS write is done (global stores may still be in flight)
+        __builtin_amdgcn_s_barrier();
+        const int v = *(volatile int *)slot;
+        return __builtin_amdgcn_readfirstlane(v);
+    }
+    __device__ __forceinline__ int first(const PassQueues &pq, int *lds_word, int wave_, int lane_)
+    {
+        offsets = pq.offsets;
+        counters = pq.counters;
+        slot = lds_word;
+        nq = pq.nq;
+        wave = wave_;
+        lane = lane_;
+        q = (int)(blockIdx.x % pq.nq);
+        hops = 0;
+        pending = 0;
+        int idx = -1;
+        if (wave == 0) {
+            idx = offsets[q] + (int)(blockIdx.x / pq.nq);
+            if (idx >= offsets[q + 1]) idx = steal();
+        }
+        return publish(idx);
+    }
+    // call when an item starts: draws the ticket of the item after it
+    __device__ __forceinline__ void prefetch()
+    {
+        if (wave == 0 && lane == 0) pending = atomicAdd(counters + q, 1);
+    }
+    // call when an item is done (all of the workgroup's LDS reads issued): next item or -1
+    __device__ __forceinline__ int advance()
+    {
+        int idx = -1;
+        if (wave == 0) {
+            idx = offsets[q] + wgs_of(q) + __builtin_amdgcn_readfirstlane(pending);
+            if (idx >= offsets[q + 1]) idx = steal();
+        }
+        return publish(idx);
+    }
+    // call once, after the last item
+    __device__ __forceinline__ void finish()
+    {
+        if (wave == 0 && lane == 0) {
+            __threadfence();
+            if (atomicAdd(counters + nq, 1) == (int)gridDim.x - 1) {
+                for (int i = 0; i <= nq; i++) counters[i] = 0;
+                __threadfence();
+            }
+        }
     }
 };
 

@@ -4,20 +4,32 @@
 // One work item = 128 query rows of one (sequence, head).  A workgroup of 4 wavefronts
 // takes items from the longest-first queues until they are empty.  Each wavefront owns 32
 // query rows and keeps their Q in registers.  Key/value tiles of 64 rows go straight from
-// global memory into swizzled LDS tiles (no staging registers), double-buffered: the next
-// tile is in flight while this one is consumed, one barrier per tile.
+// global memory into swizzled LDS tiles (no staging registers), double-buffered, one barrier
+// per tile.
+//
 // The score block is computed TRANSPOSED, S^T = K Q^T, so that in the 32x32 accumulator a
 // lane holds one query (its column) and 16 keys: the row-wise softmax is a reduction over a
 // lane's own registers plus one exchange with the lane 32 away, and the exponentiated block,
 // rounded to bf16, is directly the B operand of O^T += V^T P^T.  V^T fragments come from
 // the row-major V tile through the LDS transpose read.  The running output is rescaled only
 // when some row's maximum actually grew.
+//
+// A wavefront walks the keys in blocks of 32 (two per tile) as a software pipeline: iteration
+// c issues the matrix instructions of S(c+1) and of O += P(c-1) V(c-1) and, between them, the
+// softmax arithmetic of block c, so that the matrix pipe and the vector pipe of the SIMD work
+// at the same time inside one wavefront (the file is compiled with the compiler's
+// pre-allocation schedulers off: the order written here is the order executed).  The K tiles
+// therefore run one tile ahead of the V tiles: between the barriers of tile t and t+1 the
+// wavefronts read K tile t+1 and V tile t while K tile t+2 and V tile t+1 are in flight.
 #include <type_traits>
 
 #include "attn_common.h"
 
 namespace flexsp {
 namespace {
+
+template <int V>
+using ic = std::integral_constant<int, V>;
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
@@ -26,7 +38,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     constexpr int KS = D / 16;                  // k steps of the score product
     constexpr int DB = D / 32;                  // 32-wide blocks of the head dim
     constexpr int TILE = kFwdBk * L::ROWB;      // bytes of one 64-row tile
-    // [buffer][K | V]
+    constexpr int NCP = 2 * kFwdBk * L::CH / kThreads;  // copy instructions per wavefront for a K and a V tile
+    constexpr int NSLOT = KS + 2 * DB;          // matrix instructions of one pipeline iteration
+    static_assert(NSLOT == 2 * NCP, "one copy instruction per two matrix instructions");
+    // [K buffer 0 | K buffer 1 | V buffer 0 | V buffer 1]
     __shared__ __attribute__((aligned(1024))) char smem[4 * TILE];
 
     const int tid = threadIdx.x;
@@ -34,10 +49,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     LaneOffsets<D> lo;
     lo.init(lane0);
+    __shared__ int deal_word;
     ItemDealer deal;
-    deal.init(a.pq);
 
-    for (int item = deal.next(); item >= 0; item = deal.next()) {
+    for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
+        deal.prefetch();
         const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
@@ -53,17 +69,22 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
 
         const uint32_t goffk = tile_goff<D>(a.k_st, wave, lane), goffv = tile_goff<D>(a.v_st, wave, lane);
-        auto prefetch = [&](int t, int buf) {
-            char *dk = smem + buf * 2 * TILE, *dv = dk + TILE;
-            if ((t + 1) * kFwdBk <= s) {  // whole tile inside the sequence
-                load_tile_async_fast<D, kFwdBk>(dk, kbase + (int64_t)t * kFwdBk * a.k_st, a.k_st, goffk, wave);
-                load_tile_async_fast<D, kFwdBk>(dv, vbase + (int64_t)t * kFwdBk * a.v_st, a.v_st, goffv, wave);
-            } else {
-                load_tile_async<D, kFwdBk>(dk, kbase, a.k_st, t * kFwdBk, s - 1, wave, lane);
-                load_tile_async<D, kFwdBk>(dv, vbase, a.v_st, t * kFwdBk, s - 1, wave, lane);
-            }
+        // whole-tile copies (all of this wavefront's copy instructions back to back)
+        auto prefetch_k = [&](int t, int buf) {
+            char *dst = smem + buf * TILE;
+            if ((t + 1) * kFwdBk <= s)  // whole tile inside the sequence
+                load_tile_async_fast<D, kFwdBk>(dst, kbase + (int64_t)t * kFwdBk * a.k_st, a.k_st, goffk, wave);
+            else
+                load_tile_async<D, kFwdBk>(dst, kbase, a.k_st, t * kFwdBk, s - 1, wave, lane);
         };
-        prefetch(0, 0);
+        auto prefetch_v = [&](int t, int buf) {
+            char *dst = smem + (2 + buf) * TILE;
+            if ((t + 1) * kFwdBk <= s)
+                load_tile_async_fast<D, kFwdBk>(dst, vbase + (int64_t)t * kFwdBk * a.v_st, a.v_st, goffv, wave);
+            else
+                load_tile_async<D, kFwdBk>(dst, vbase, a.v_st, t * kFwdBk, s - 1, wave, lane);
+        };
+        prefetch_k(0, 0);
 
         // ---- Q fragments (B operand: column = query row, k = head dim), kept in registers
         const int qrow = q0 + wave * 32 + r;  // row inside the sequence
@@ -79,107 +100,236 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                 qf[ks] = f.v;
             }
         }
+        // last 32-key block this wavefront has to look at (-1: none, its rows lie past the sequence)
+        const int cmax = wq_lo >= s ? -1 : (a.causal ? min((kv_end - 1) >> 5, wq_lo >> 5) : (kv_end - 1) >> 5);
+        const int cmask = a.causal ? (wq_lo >> 5) : ((s - 1) >> 5);  // the block that needs masking
+        const int lim = a.causal ? qrow : s - 1;                      // largest visible key of this lane's row
 
         f32x16 oacc[DB];
 #pragma unroll
         for (int db = 0; db < DB; db++)
 #pragma unroll
             for (int i = 0; i < 16; i++) oacc[db][i] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f, moff = 0.f;
+        float m_run = -INFINITY, l_run = 0.f;
+        f32x16 sacc[2];     // S of block c in sacc[c & 1]
+        uint32_t pk[2][8];  // P of block c (bf16 pairs) in pk[c & 1]
 
-        auto step = [&](auto bufc, int t) {
-            constexpr int BUF = decltype(bufc)::value;
-            const char *sK = smem + BUF * 2 * TILE;
-            const char *sV = sK + TILE;
-            const int kv0 = t * kFwdBk;
-            lo.pin();
-            wait_vmem();      // this wavefront's share of tile t has landed
-            __syncthreads();  // everybody's has, and everybody is done with tile t-1
-            if (t + 1 < ntiles) prefetch(t + 1, BUF ^ 1);
-            // wavefronts whose rows all lie above this tile (causal) have nothing to do
-            if (a.causal && kv0 > wq_lo + 31) return;
-
-            // ---- S^T = K Q^T : two 32-key blocks
-            f32x16 sacc[2];
+        // ---------------- the three stages of a block, one after the other (pipeline ends) -----
+        // S(c) = K(c) Q^T; `sK` points at the block's first row inside its K tile
+        auto scores = [&](f32x16 &sa, const char *sK) {
+            constexpr int AH = 4;
+            bf16x8 kf[KS];
 #pragma unroll
-            for (int kb = 0; kb < 2; kb++)
+            for (int i = 0; i < 16; i++) sa[i] = 0.f;
 #pragma unroll
-                for (int i = 0; i < 16; i++) sacc[kb][i] = 0.f;
+            for (int j = 0; j < AH && j < KS; j++) kf[j] = lds_nat(sK, lo.nat[j]);
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++)
-#pragma unroll
-                for (int kb = 0; kb < 2; kb++)
-                    sacc[kb] = mfma32(lds_nat(sK, kb * 32 * L::ROWB + lo.nat[ks]), qf[ks], sacc[kb]);
-            // ---- mask (only tiles that touch the diagonal or the end of the sequence)
-            const bool need_mask = a.causal ? (kv0 + kFwdBk - 1 > wq_lo) : (kv0 + kFwdBk > s);
-            if (need_mask) {
-                const int lim = a.causal ? qrow : s - 1;  // largest visible key
-#pragma unroll
-                for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-                    for (int i = 0; i < 16; i++) {
-                        int kv = kv0 + kb * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
-                        if (kv > lim) sacc[kb][i] = -INFINITY;
-                    }
+            for (int j = 0; j < KS; j++) {
+                if (j + AH < KS) kf[j + AH] = lds_nat(sK, lo.nat[j + AH]);
+                sa = mfma32(kf[j], qf[j], sa);
             }
-            // ---- online softmax (one query per lane, 32 of its keys here, 32 in lane^32)
-            float mx = fmaxf(sacc[0][0], sacc[1][0]);
+        };
+        // O^T += V(c)^T P(c)^T
+        auto pv = [&](const uint32_t (&p)[8], const char *sV) {
+            constexpr int AH = 4, N = 2 * DB;
+            bf16x8 vf[N];
+            auto vread = [&](int j) {
+                const int rowoff = (j / DB) * 16 * L::ROWB;
+                return lds_tr(sV, rowoff + lo.tr[j % DB][0], rowoff + lo.tr[j % DB][1]);
+            };
 #pragma unroll
-            for (int i = 1; i < 16; i++) mx = fmaxf(mx, fmaxf(sacc[0][i], sacc[1][i]));
-            mx = halves_max(mx);
-            if (__builtin_amdgcn_ballot_w64(mx > m_run) != 0) {  // some row's maximum grew
-                const float m_new = fmaxf(m_run, mx);
+            for (int j = 0; j < AH && j < N; j++) vf[j] = vread(j);
+#pragma unroll
+            for (int j = 0; j < N; j++) {
+                if (j + AH < N) vf[j + AH] = vread(j + AH);
+                const int st = j / DB;
+                Frag8 pf;
+                pf.u = u32x4{p[4 * st], p[4 * st + 1], p[4 * st + 2], p[4 * st + 3]};
+                oacc[j % DB] = mfma32(vf[j], pf.v, oacc[j % DB]);
+            }
+        };
+        // Online-softmax bookkeeping shared by both forms of an iteration.
+        //   row maximum of a block: own 16 keys, then the other half-wave's
+        auto block_max = [&](const f32x16 &sa) {
+            float mx = fmaxf(sa[0], sa[1]);
+#pragma unroll
+            for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sa[i], sa[i + 1]));
+            return halves_max(mx);
+        };
+        //   after the iteration's O += P V: rescale if some row's maximum grew, fold in the row sums
+        auto finish_block = [&](float m_new, float psum) {
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
                 const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_l2);
-                m_run = m_new;
-                moff = m_new * a.scale_l2;
                 l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < DB; db++)
 #pragma unroll
                     for (int i = 0; i < 16; i++) oacc[db][i] *= alpha;
+                m_run = m_new;
             }
-            float psum = 0.f;
-            uint32_t pk[2][8];
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i], a.scale_l2, -moff));
-                    float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][i + 1], a.scale_l2, -moff));
-                    psum += p0 + p1;  // fp32: the log-sum-exp feeds the backward recomputation
-                    pk[kb][i >> 1] = pack_bf16x2(p0, p1);
-                }
-            l_run += psum;
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-                for (int hf = 0; hf < 2; hf++) {
-                    Frag8 pf;
-                    pf.u = u32x4{pk[kb][4 * hf], pk[kb][4 * hf + 1], pk[kb][4 * hf + 2], pk[kb][4 * hf + 3]};
-                    const int rowoff = (kb * 32 + hf * 16) * L::ROWB;
-#pragma unroll
-                    for (int db = 0; db < DB; db++)
-                        oacc[db] = mfma32(lds_tr(sV, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), pf.v, oacc[db]);
-                }
+            l_run += psum;  // fp32: the log-sum-exp feeds the backward recomputation
         };
 
-        for (int t = 0; t < ntiles; t += 2) {
-            step(std::integral_constant<int, 0>{}, t);
-            if (t + 1 < ntiles) step(std::integral_constant<int, 1>{}, t + 1);
+        // ---------------- iteration c, general form: any subset of the three stages ------------
+        // S(c+1), softmax(c), O += P(c-1) V(c-1), done one after the other.  Used where the pipeline
+        // fills and drains and for the masked block.  sK / sV: first row of block c+1 / c-1.
+        auto iter_slow = [&](auto cpc, int c, const char *sK, const char *sV) {
+            constexpr int CP = decltype(cpc)::value;  // c & 1
+            if (c + 1 <= cmax) scores(sacc[CP ^ 1], sK);
+            float m_new = m_run, psum = 0.f;
+            if (c <= cmax) {
+                f32x16 &sa = sacc[CP];
+                if (c == cmask) {
+#pragma unroll
+                    for (int i = 0; i < 16; i++) {
+                        const int kv = c * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
+                        if (kv > lim) sa[i] = -INFINITY;
+                    }
+                }
+                m_new = fmaxf(m_run, block_max(sa));
+                const float moff = m_new * a.scale_l2;
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[i], a.scale_l2, -moff));
+                    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[i + 1], a.scale_l2, -moff));
+                    psum += p0 + p1;
+                    pk[CP][i >> 1] = pack_bf16x2(p0, p1);
+                }
+            }
+            if (c >= 1 && c - 1 <= cmax) pv(pk[CP ^ 1], sV);
+            if (c <= cmax) finish_block(m_new, psum);
+        };
+
+        // ---------------- iteration c, pipelined form: all three stages, interleaved -----------
+        // Slot j issues matrix instruction j (first the KS of S(c+1), then the 2*DB of O += P V),
+        // the LDS read of the operand AH slots ahead, every second slot one copy instruction of the
+        // tiles in flight (PF; K tile t+2 and V tile t+1), and a share of the softmax arithmetic of
+        // block c: the row maximum in slots 0 and 1, the 16 exponentials over the remaining slots.
+        // One basic block on purpose: a branch inside it would let the optimiser sink the softmax
+        // arithmetic below the matrix instructions.
+        auto iter_fast = [&](auto cpc, auto kbc, auto vbc, auto pfc, int t) {
+            constexpr int CP = decltype(cpc)::value;  // c & 1; blocks c+1 and c-1 start at row 0 (CP = 1) or 32 of their tile
+            constexpr int KB = decltype(kbc)::value, VB = decltype(vbc)::value;
+            constexpr bool PF = decltype(pfc)::value != 0;
+            constexpr int AH = 4;
+            const char *sK = smem + KB * TILE + (CP ? 0 : 32 * L::ROWB);
+            const char *sV = smem + (2 + VB) * TILE + (CP ? 0 : 32 * L::ROWB);
+            f32x16 &sn = sacc[CP ^ 1];
+            const f32x16 &sc = sacc[CP];
+            const uint32_t(&pp)[8] = pk[CP ^ 1];
+            bf16x8 fr[NSLOT];
+            auto rd = [&](int j) {
+                if (j < KS) return lds_nat(sK, lo.nat[j < KS ? j : 0]);
+                const int rowoff = ((j - KS) / DB) * 16 * L::ROWB;
+                return lds_tr(sV, rowoff + lo.tr[(j - KS) % DB][0], rowoff + lo.tr[(j - KS) % DB][1]);
+            };
+#pragma unroll
+            for (int j = 0; j < AH; j++) fr[j] = rd(j);
+#pragma unroll
+            for (int i = 0; i < 16; i++) sn[i] = 0.f;
+            float mx = 0.f, m_new = 0.f, moff = 0.f, psum = 0.f, pprev = 0.f;
+#pragma unroll
+            for (int j = 0; j < NSLOT; j++) {
+                if (j + AH < NSLOT) fr[j + AH] = rd(j + AH);
+                if (j < KS) {
+                    sn = mfma32(fr[j], qf[j < KS ? j : 0], sn);
+                } else {
+                    const int st = (j - KS) / DB;
+                    Frag8 pf;
+                    pf.u = u32x4{pp[4 * st], pp[4 * st + 1], pp[4 * st + 2], pp[4 * st + 3]};
+                    oacc[(j - KS) % DB] = mfma32(fr[j], pf.v, oacc[(j - KS) % DB]);
+                }
+                if (PF && (j & 1)) {
+                    const int n = j >> 1;
+                    if (n < NCP / 2)
+                        load_tile_async_fast_one<D>(smem + (KB ^ 1) * TILE, kbase + (int64_t)(t + 2) * kFwdBk * a.k_st,
+                                                    a.k_st, goffk, wave, n);
+                    else
+                        load_tile_async_fast_one<D>(smem + (2 + (VB ^ 1)) * TILE, vbase + (int64_t)(t + 1) * kFwdBk * a.v_st,
+                                                    a.v_st, goffv, wave, n - NCP / 2);
+                }
+                if (j == 0) {
+                    mx = fmaxf(sc[0], sc[1]);
+#pragma unroll
+                    for (int i = 2; i < 8; i += 2) mx = fmaxf(mx, fmaxf(sc[i], sc[i + 1]));
+                } else if (j == 1) {
+#pragma unroll
+                    for (int i = 8; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sc[i], sc[i + 1]));
+                    m_new = fmaxf(m_run, halves_max(mx));
+                    moff = m_new * a.scale_l2;
+                } else {
+                    constexpr int NE = NSLOT - 2;  // slots that carry exponentials
+#pragma unroll
+                    for (int e = ((j - 2) * 16) / NE; e < ((j - 1) * 16) / NE; e++) {
+                        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], a.scale_l2, -moff));
+                        psum += p;
+                        if (e & 1) {
+                            pk[CP][e >> 1] = pack_bf16x2(pprev, p);
+                            // keeps the arithmetic of this pair here: the optimiser would otherwise sink
+                            // it to the pair's first use, below the matrix instructions it is to overlap
+                            asm volatile("" : "+v"(pk[CP][e >> 1]));
+                        } else {
+                            pprev = p;
+                        }
+                    }
+                }
+            }
+            asm volatile("" : "+v"(psum));  // the row-sum additions stay above, among the matrix instructions
+            finish_block(m_new, psum);
+        };
+
+        // ---------------- pipeline fill: K tile 0 -> S(0), then iteration 0 --------------------
+        wait_vmem();
+        __syncthreads();
+        if (ntiles > 1) prefetch_k(1, 1);
+        prefetch_v(0, 0);
+        if (cmax >= 0) scores(sacc[0], smem);
+        iter_slow(ic<0>{}, 0, smem + 32 * L::ROWB, smem);
+
+        // ---------------- window t: iterations 2t+1 and 2t+2 ------------------------------------
+        // Steady state: both iterations pipelined, and the copies of K tile t+2 and V tile t+1 (both
+        // wholly inside the sequence) ride along with iteration 2t+1.  No branch but the rare rescale.
+        auto window_steady = [&](auto vbc, int t) {
+            constexpr int VB = decltype(vbc)::value, KB = VB ^ 1;  // V tile t in VB, K tile t+1 in KB
+            lo.pin();
+            wait_vmem();      // this wavefront's share of K tile t+1 and V tile t has landed
+            __syncthreads();  // everybody's has, and everybody is done with K tile t and V tile t-1
+            iter_fast(ic<1>{}, ic<KB>{}, ic<VB>{}, ic<1>{}, t);
+            iter_fast(ic<0>{}, ic<KB>{}, ic<VB>{}, ic<0>{}, t);
+        };
+        // General form (pipeline fill and drain, masked block, ragged last tile): the copies go out in
+        // one go after the barrier and the stages of an iteration run one after the other.  One copy
+        // of the code for both buffer parities: the tile addresses are run-time values here.
+        auto window = [&](int t) {
+            const int vb = t & 1, kb = vb ^ 1;  // V tile t in vb, K tile t+1 in kb
+            lo.pin();
+            wait_vmem();      // this wavefront's share of K tile t+1 and V tile t has landed
+            __syncthreads();  // everybody's has, and everybody is done with K tile t and V tile t-1
+            if (t + 2 < ntiles) prefetch_k(t + 2, kb ^ 1);
+            if (t + 1 < ntiles) prefetch_v(t + 1, vb ^ 1);
+            const char *sK = smem + kb * TILE, *sV = smem + (2 + vb) * TILE;
+            iter_slow(ic<1>{}, 2 * t + 1, sK, sV);
+            iter_slow(ic<0>{}, 2 * t + 2, sK + 32 * L::ROWB, sV + 32 * L::ROWB);
+        };
+        // windows [0, tsteady) are steady ones: t + 3 <= ntiles, (t + 3) * kFwdBk <= s, 2t + 3 <= cmax
+        const int tsteady = max(0, min(min(ntiles, s / kFwdBk) - 2, (cmax - 1) >> 1));
+        int t = 0;
+        for (; t + 1 < tsteady; t += 2) {
+            window_steady(ic<0>{}, t);
+            window_steady(ic<1>{}, t + 1);
         }
+        for (; t < ntiles; t++) window(t);
 
         // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
         const float l_tot = halves_sum(l_run);
         if (qrow < s && hl == 0) a.lse_out[(int64_t)h * a.T + tok0 + qrow] = m_run * a.scale + __logf(l_tot);
-        // O goes out through the tile buffer the last step did not use (every wavefront is past the
-        // barrier of the last step, so nobody reads that buffer any more)
+        barrier_lds_only();  // every wavefront is done reading tiles: O is staged through the K buffers
         if (wq_lo < s)
-            store_rowT_bf16_lds<DB>(smem + (ntiles & 1) * 2 * TILE + wave * (32 * L::ROWB),
-                                    a.out_o + (tok0 + wq_lo) * a.o_st + (int64_t)h * a.o_sh, a.o_st,
-                                    min(32, s - wq_lo), oacc, 1.0f / l_tot, lane);
-        barrier_lds_only();  // the LDS buffers are reused by the next item
+            store_rowT_bf16_lds<DB>(smem + wave * (32 * L::ROWB), a.out_o + (tok0 + wq_lo) * a.o_st + (int64_t)h * a.o_sh,
+                                    a.o_st, min(32, s - wq_lo), oacc, 1.0f / l_tot, lane);
+        // deal.advance() holds the barrier after which the LDS buffers are reused by the next item
     }
+    deal.finish();
 }
 
 }  // namespace

@@ -196,7 +196,8 @@ bool view_ok(const flexsp_tensor &t)
     if (((uintptr_t)t.ptr & 15) != 0) return false;
     if (t.stride_token <= 0 || t.stride_head <= 0) return false;
     if ((t.stride_token % 8) != 0 || (t.stride_head % 8) != 0) return false;
-    if (t.stride_token > 0x3fffffff || t.stride_head > 0x3fffffff) return false;  // kernels use 32-bit strides
+    // kernels use 32-bit strides, and 32-bit per-lane byte offsets that span up to 64 token rows
+    if (t.stride_token > (1 << 24) || t.stride_head > 0x3fffffff) return false;
     return true;
 }
 

@@ -52,7 +52,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     __shared__ int deal_word;
     ItemDealer deal;
 
-    for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
+    int item = deal.first(a.pq, &deal_word, wave, lane0);
+    for (; item >= 0; item = deal.advance()) {
         deal.prefetch();
         const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
@@ -323,7 +324,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
         const float l_tot = halves_sum(l_run);
         if (qrow < s && hl == 0) a.lse_out[(int64_t)h * a.T + tok0 + qrow] = m_run * a.scale + __logf(l_tot);
-        barrier_lds_only();  // every wavefront is done reading tiles: O is staged through the K buffers
+        // O is staged through the K buffers without a barrier: no wavefront reads a K tile after the
+        // barrier of the last window (the scores of the last blocks were issued in the window before),
+        // and this wavefront is past that barrier, so every wavefront has reached it
         if (wq_lo < s)
             store_rowT_bf16_lds<DB>(smem + wave * (32 * L::ROWB), a.out_o + (tok0 + wq_lo) * a.o_st + (int64_t)h * a.o_sh,
                                     a.o_st, min(32, s - wq_lo), oacc, 1.0f / l_tot, lane);

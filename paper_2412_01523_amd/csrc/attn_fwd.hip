@@ -157,7 +157,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             for (int i = 2; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sa[i], sa[i + 1]));
             return halves_max(mx);
         };
-        //   after the iteration's O += P V: rescale if some row's maximum grew, fold in the row sums
+        //   the reference value subtracted from a block's scores: the running one, which only moves
+        //   when some row's maximum exceeds it by more than 8 in the exponent's units (P then stays
+        //   below 2^8: exact in bf16 and fp32 alike, and the final O / l and LSE do not depend on
+        //   the reference).  Without the slack the first blocks of every item, where the maxima still
+        //   grow a little with each block, would rescale O (64 multiplications) almost every time.
+        const float slack = 8.0f / a.scale_l2;
+        auto reference = [&](float mx) {
+            const bool move = __builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0;
+            return move ? fmaxf(m_run, mx) : m_run;
+        };
+        //   after the iteration's O += P V: rescale if the reference moved, fold in the row sums
         auto finish_block = [&](float m_new, float psum) {
             if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
                 const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_l2);
@@ -187,7 +197,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                         if (kv > lim) sa[i] = -INFINITY;
                     }
                 }
-                m_new = fmaxf(m_run, block_max(sa));
+                m_new = reference(block_max(sa));
                 const float moff = m_new * a.scale_l2;
 #pragma unroll
                 for (int i = 0; i < 16; i += 2) {
@@ -256,7 +266,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                 } else if (j == 1) {
 #pragma unroll
                     for (int i = 8; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sc[i], sc[i + 1]));
-                    m_new = fmaxf(m_run, halves_max(mx));
+                    m_new = reference(halves_max(mx));
                     moff = m_new * a.scale_l2;
                 } else {
                     constexpr int NE = NSLOT - 2;  // slots that carry exponentials

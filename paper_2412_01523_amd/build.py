@@ -36,7 +36,7 @@ FLAGS = [
 # use, which exposes the full LDS latency once per matrix instruction; with them off the order
 # of the source is the order of the code.
 SOURCE_ORDER = ["-mllvm", "-pre-RA-sched=source", "-mllvm", "-enable-misched=false"]
-PER_SOURCE = {"attn_fwd.hip": SOURCE_ORDER}
+PER_SOURCE = {"attn_fwd.hip": SOURCE_ORDER, "attn_bwd.hip": SOURCE_ORDER}
 
 
 def _hipcc() -> str:

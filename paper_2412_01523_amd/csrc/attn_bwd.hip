@@ -20,6 +20,11 @@
 namespace flexsp {
 namespace {
 
+// LDS fragments are read this many matrix instructions ahead of the one that uses them (the file is
+// compiled in source order, like the forward kernel: the schedulers would sink the reads back)
+constexpr int kReadAhead = 4;
+
+
 // ------------------------------------------------------------------------------ delta
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const AttnArgs a)
@@ -167,10 +172,21 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 f32x16 sacc, pacc;
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
+                {
+                    // fragment n: k step n / 2 of the Q tile (n even) or the dO tile (n odd); read AH ahead
+                    constexpr int AH = kReadAhead, N = 2 * KS;
+                    bf16x8 fr[N];
+                    auto rd = [&](int n) { return lds_nat((n & 1) ? sG : sQ, j * 32 * L::ROWB + lo.nat[n >> 1]); };
 #pragma unroll
-                for (int ks = 0; ks < KS; ks++) {
-                    sacc = mfma32(lds_nat(sQ, j * 32 * L::ROWB + lo.nat[ks]), kf[ks], sacc);
-                    pacc = mfma32(lds_nat(sG, j * 32 * L::ROWB + lo.nat[ks]), vf[ks], pacc);
+                    for (int n = 0; n < AH; n++) fr[n] = rd(n);
+#pragma unroll
+                    for (int n = 0; n < N; n++) {
+                        if (n + AH < N) fr[n + AH] = rd(n + AH);
+                        if (n & 1)
+                            pacc = mfma32(fr[n], vf[n >> 1], pacc);
+                        else
+                            sacc = mfma32(fr[n], kf[n >> 1], sacc);
+                    }
                 }
                 // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e
                 const bool masked = (a.causal && my_lo < wk_lo + 31) || (my_lo + 32 > s);
@@ -221,12 +237,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                     f[0].u = *(const u32x4 *)(slot);
                     f[1].u = *(const u32x4 *)(slot + 1024);
                 }
+                {
+                    constexpr int AH = kReadAhead, N = 2 * DB;  // fragment n: query half n / DB, head-dim block n % DB
+                    bf16x8 fr[N];
+                    auto rd = [&](int n) {
+                        const int rowoff = (qb * 32 + (n / DB) * 16) * L::ROWB;
+                        return lds_tr(sX, rowoff + lo.tr[n % DB][0], rowoff + lo.tr[n % DB][1]);
+                    };
 #pragma unroll
-                for (int hf = 0; hf < 2; hf++) {
-                    const int rowoff = (qb * 32 + hf * 16) * L::ROWB;
+                    for (int n = 0; n < AH; n++) fr[n] = rd(n);
 #pragma unroll
-                    for (int d = 0; d < DB; d++)
-                        accT[d] = mfma32(lds_tr(sX, rowoff + lo.tr[d][0], rowoff + lo.tr[d][1]), f[hf].v, accT[d]);
+                    for (int n = 0; n < N; n++) {
+                        if (n + AH < N) fr[n + AH] = rd(n + AH);
+                        accT[n % DB] = mfma32(fr[n], f[n / DB].v, accT[n % DB]);
+                    }
                 }
             }
         };
@@ -344,10 +368,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                 f32x16 sacc, pacc;
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
+                {
+                    constexpr int AH = kReadAhead, N = 2 * KS;  // fragment n: k step n / 2 of the K tile (n even) or the V tile (n odd)
+                    bf16x8 fr[N];
+                    auto rd = [&](int n) { return lds_nat((n & 1) ? sV : sK, kb * 32 * L::ROWB + lo.nat[n >> 1]); };
 #pragma unroll
-                for (int ks = 0; ks < KS; ks++) {
-                    sacc = mfma32(lds_nat(sK, kb * 32 * L::ROWB + lo.nat[ks]), qf[ks], sacc);
-                    pacc = mfma32(lds_nat(sV, kb * 32 * L::ROWB + lo.nat[ks]), gf[ks], pacc);
+                    for (int n = 0; n < AH; n++) fr[n] = rd(n);
+#pragma unroll
+                    for (int n = 0; n < N; n++) {
+                        if (n + AH < N) fr[n + AH] = rd(n + AH);
+                        if (n & 1)
+                            pacc = mfma32(fr[n], gf[n >> 1], pacc);
+                        else
+                            sacc = mfma32(fr[n], qf[n >> 1], sacc);
+                    }
                 }
                 uint32_t dd[8];
                 auto dsfn = [&](auto maskc) {
@@ -369,14 +403,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                 else
                     dsfn(std::false_type{});
                 // dQ^T += K^T dS^T
+                {
+                    constexpr int AH = kReadAhead, N = 2 * DB;  // fragment n: key half n / DB, head-dim block n % DB
+                    bf16x8 fr[N];
+                    auto rd = [&](int n) {
+                        const int rowoff = (kb * 32 + (n / DB) * 16) * L::ROWB;
+                        return lds_tr(sK, rowoff + lo.tr[n % DB][0], rowoff + lo.tr[n % DB][1]);
+                    };
 #pragma unroll
-                for (int hf = 0; hf < 2; hf++) {
-                    Frag8 df;
-                    df.u = u32x4{dd[4 * hf], dd[4 * hf + 1], dd[4 * hf + 2], dd[4 * hf + 3]};
-                    const int rowoff = (kb * 32 + hf * 16) * L::ROWB;
+                    for (int n = 0; n < AH; n++) fr[n] = rd(n);
 #pragma unroll
-                    for (int db = 0; db < DB; db++)
-                        dqT[db] = mfma32(lds_tr(sK, rowoff + lo.tr[db][0], rowoff + lo.tr[db][1]), df.v, dqT[db]);
+                    for (int n = 0; n < N; n++) {
+                        if (n + AH < N) fr[n + AH] = rd(n + AH);
+                        const int hf = n / DB;
+                        Frag8 df;
+                        df.u = u32x4{dd[4 * hf], dd[4 * hf + 1], dd[4 * hf + 2], dd[4 * hf + 3]};
+                        dqT[n % DB] = mfma32(fr[n], df.v, dqT[n % DB]);
+                    }
                 }
             }
         };

@@ -138,6 +138,8 @@ def main() -> int:
                     help="lognormal-32k | pareto-64k | single-128k | bimodal-256k-gqa | tiny-436")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-permute-leg", action="store_true")
+    ap.add_argument("--reuse-plan", action="store_true",
+                    help="build the tile plan once, outside the timed steps (a plan serves every layer of a micro-batch)")
     ap.add_argument("--attention-only", action="store_true", help="step = plan + fwd + bwd (no permutes)")
     ap.add_argument("--cost-model", action="store_true",
                     help="only the cost-model leg: time attention fwd+bwd on 24 synthetic batches, fit the "
@@ -200,8 +202,10 @@ def main() -> int:
     v3 = lambda t: t.view(T, t.shape[2], D)
     stream = torch.cuda.current_stream()
 
+    shared_plan = fx.Plan(ctx, cu, Hq, Hkv, D, True) if args.reuse_plan else None
+
     def step():
-        plan = fx.Plan(ctx, cu, Hq, Hkv, D, True)
+        plan = shared_plan if args.reuse_plan else fx.Plan(ctx, cu, Hq, Hkv, D, True)
         if not args.attention_only:
             fx.flexsp_pack(ctx, xq, sq, P, stream)
             fx.flexsp_pack(ctx, xk, sk, P, stream)
@@ -227,7 +231,8 @@ def main() -> int:
         plans.append(step())
     torch.cuda.synchronize()
     for p in plans:
-        p.close()
+        if p is not shared_plan:
+            p.close()
     plans = []
 
     ctx.profile_start(16 * max(args.steps, 1))
@@ -239,7 +244,8 @@ def main() -> int:
     t1 = time.perf_counter()
     prof = ctx.profile_stop()
     for p in plans:
-        p.close()
+        if p is not shared_plan:
+            p.close()
 
     ms_step = (t1 - t0) * 1e3 / max(args.steps, 1)
     tflops = (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12
@@ -265,7 +271,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "tokens": T, "sequences": len(lens), "max_len": max(lens),
                    "hq": Hq, "hkv": Hkv, "head_dim": D, "causal": True, "sp_degree": P,
-                   "step": "plan+fwd+bwd" if args.attention_only else "plan+4 pack+fwd+bwd+4 unpack",
+                   "step": ("" if args.reuse_plan else "plan+") + ("fwd+bwd" if args.attention_only else "4 pack+fwd+bwd+4 unpack"),
                    "flops_fwd_bwd": f_fwd + f_bwd, "seed": cfg.seed},
         "frac_of_bf16_mfma_peak": tflops * 1e12 / BF16_MFMA_PEAK,
         "attention_kernels_only": {"ms": attn_ms, "tflops": (f_fwd + f_bwd) / (attn_ms * 1e-3) / 1e12,

@@ -196,7 +196,7 @@ enum {
     FLEXSP_K_PACK = 0,
     FLEXSP_K_UNPACK = 1,
     FLEXSP_K_FWD = 2,
-    FLEXSP_K_BWD_DELTA = 3,
+    FLEXSP_K_BWD_DELTA = 3, /* reserved: the row-dot preprocessing is part of the dQ kernel, never launched */
     FLEXSP_K_BWD_DKV = 4,
     FLEXSP_K_BWD_DQ = 5,
     FLEXSP_K_COUNT = 6

@@ -25,36 +25,6 @@ namespace {
 constexpr int kReadAhead = 4;
 
 
-// ------------------------------------------------------------------------------ delta
-template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const AttnArgs a)
-{
-    constexpr int LPR = D / 8;        // lanes per row
-    constexpr int RPB = 256 / LPR;    // rows per block
-    const int64_t rows = (int64_t)a.T * a.Hq;
-    const int sub = threadIdx.x % LPR;
-    // block-uniform loop: lanes past the end still take part in the shuffles
-    for (int64_t base = (int64_t)blockIdx.x * RPB; base < rows; base += (int64_t)gridDim.x * RPB) {
-        const int64_t row = base + threadIdx.x / LPR;
-        const bool ok = row < rows;
-        const int64_t t = ok ? row / a.Hq : 0;
-        const int h = ok ? (int)(row % a.Hq) : 0;
-        u32x4 x = *(const u32x4 *)(a.o + t * a.o_st + (int64_t)h * a.o_sh + sub * 8);
-        u32x4 y = *(const u32x4 *)(a.dO + t * a.do_st + (int64_t)h * a.do_sh + sub * 8);
-        float acc = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-            acc += bf16_lo(x[i]) * bf16_lo(y[i]) + bf16_hi(x[i]) * bf16_hi(y[i]);
-#pragma unroll
-        for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-        if (ok && sub == 0) {
-            a.delta_out[(int64_t)h * a.T + t] = acc;
-            // the log-sum-exp in base 2, so the recomputation is one fma + exp2 per score
-            a.lse_out[(int64_t)h * a.T + t] = a.lse_in[(int64_t)h * a.T + t] * 1.4426950408889634f;
-        }
-    }
-}
-
 // ------------------------------------------------------------------------------ dK / dV
 // One work item = 64 keys of one (sequence, kv head).  The accumulators of 32 keys x D for both
 // dK and dV, next to the K and V fragments, would take more than half of the register file and
@@ -326,9 +296,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         const int wq_lo = q0 + wave * 32;
         const bool qok = qrow < s;
         bf16x8 qf[KS], gf[KS];  // B operands: column = query row, k = head dim
+        // delta = dO . O of the row (the backward's preprocessing step, done here because this kernel
+        // has the row's dO in registers anyway): this lane's half of the row, then the other half-wave's
+        float dpart = 0.f;
         {
             const uint16_t *qp = a.q + (tok0 + (qok ? qrow : 0)) * a.q_st + (int64_t)h * a.q_sh + 8 * hl;
             const uint16_t *gp = a.dO + (tok0 + (qok ? qrow : 0)) * a.do_st + (int64_t)h * a.do_sh + 8 * hl;
+            const uint16_t *op = a.o + (tok0 + (qok ? qrow : 0)) * a.o_st + (int64_t)h * a.o_sh + 8 * hl;
+            // all loads first, then the arithmetic (the file is compiled in source order: a dot product
+            // between two loads would make the second wait for the first)
+            u32x4 ov[KS];
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) {
                 Frag8 f;
@@ -336,11 +313,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                 qf[ks] = f.v;
                 f.u = qok ? *(const u32x4 *)(gp + 16 * ks) : u32x4{0, 0, 0, 0};
                 gf[ks] = f.v;
+                ov[ks] = qok ? *(const u32x4 *)(op + 16 * ks) : u32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+                Frag8 f;
+                f.v = gf[ks];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    // (scalars first: a bit cast applied to a vector element in place reads element 0)
+                    const uint32_t gw = f.u[i], ow = ov[ks][i];
+                    dpart = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, gw), __builtin_bit_cast(bf16x2, ow),
+                                                            dpart, false);
+                }
             }
         }
-        // +inf log-sum-exp makes P = 0 for rows past the end of the sequence
-        const float lse2 = qok ? a.lse_in[(int64_t)h * a.T + tok0 + qrow] : INFINITY;
-        const float delta = qok ? a.delta_in[(int64_t)h * a.T + tok0 + qrow] : 0.f;
+        const float delta = halves_sum(dpart);
+        // the log-sum-exp in base 2, so that the recomputation is one fma + exp2 per score; +inf makes
+        // P = 0 for rows past the end of the sequence
+        const float lse2 = qok ? a.lse_in[(int64_t)h * a.T + tok0 + qrow] * 1.4426950408889634f : INFINITY;
 
         f32x16 dqT[DB];  // rows = head dim, column = query
 #pragma unroll
@@ -428,6 +419,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
             if (t + 1 < ntiles) step_fn(std::integral_constant<int, 1>{}, t + 1);
         }
 
+        // delta and the base-2 log-sum-exp are kept for the dK/dV kernel, which runs after this one
+        // (stored here, not where they are computed: a store in flight there would be waited for by
+        // the first tile's wait for its copy)
+        if (qok && hl == 0) {
+            a.delta_out[(int64_t)h * a.T + tok0 + qrow] = delta;
+            a.lse_out[(int64_t)h * a.T + tok0 + qrow] = lse2;
+        }
         if (a.grad_f32) {
             if (qok)
                 store_rowT<DB>((char *)a.dq + ((tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh) * 4, true, dqT,
@@ -444,20 +442,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
 }
 
 }  // namespace
-
-hipError_t launch_attn_bwd_delta(const AttnArgs &a, int D, hipStream_t s)
-{
-    int64_t rows = (int64_t)a.T * a.Hq;
-    int rpb = 256 / (D / 8);
-    int64_t blocks = (rows + rpb - 1) / rpb;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    if (blocks < 1) blocks = 1;
-    if (D == 128)
-        hipLaunchKernelGGL(attn_bwd_delta_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, s, a);
-    else
-        hipLaunchKernelGGL(attn_bwd_delta_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, s, a);
-    return hipGetLastError();
-}
 
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s)
 {

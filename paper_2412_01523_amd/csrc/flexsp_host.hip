@@ -568,30 +568,28 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
     a.dk_st = (int32_t)dk.stride_token; a.dk_sh = (int32_t)dk.stride_head;
     a.dv_st = (int32_t)dv.stride_token; a.dv_sh = (int32_t)dv.stride_head;
     float *lse2 = plan->delta + (size_t)plan->T * plan->Hq;
-    a.lse_in = lse;       // the preprocess kernel reads the caller's LSE ...
-    a.lse_out = lse2;     // ... and writes it in the log2 domain next to delta
-    a.delta_out = plan->delta;
-    a.delta_in = plan->delta;
     a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
     a.scale = scale; a.scale_l2 = scale * 1.4426950408889634f;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
-    {
-        Timed tm(ctx, FLEXSP_K_BWD_DELTA, s);
-        e = launch_attn_bwd_delta(a, plan->D, s);
-    }
-    if (e != hipSuccess) return hip_fail(e);
-    a.lse_in = lse2;
-    a.pq = plan->dq[FLEXSP_PASS_BWD_DKV];
-    {
-        Timed tm(ctx, FLEXSP_K_BWD_DKV, s);
-        e = launch_attn_bwd_dkv(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DKV], 2), s);
-    }
-    if (e != hipSuccess) return hip_fail(e);
+    // The dQ kernel runs first: it holds every query row's dO in registers, so it also computes
+    // delta = dO . O and the log-sum-exp in base 2 for its rows and leaves both in the plan's
+    // scratch for the dK/dV kernel (no separate preprocessing launch).
+    a.lse_in = lse;
+    a.lse_out = lse2;
+    a.delta_out = plan->delta;
     a.pq = plan->dq[FLEXSP_PASS_BWD_DQ];
     {
         Timed tm(ctx, FLEXSP_K_BWD_DQ, s);
         e = launch_attn_bwd_dq(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DQ], 2), s);
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    a.lse_in = lse2;
+    a.delta_in = plan->delta;
+    a.pq = plan->dq[FLEXSP_PASS_BWD_DKV];
+    {
+        Timed tm(ctx, FLEXSP_K_BWD_DKV, s);
+        e = launch_attn_bwd_dkv(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DKV], 2), s);
     }
     return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
 }

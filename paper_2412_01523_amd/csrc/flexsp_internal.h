@@ -51,7 +51,6 @@ struct AttnArgs {
 hipError_t launch_pack(const void *src, void *dst, int64_t T, int H, int D, int P, int eb,
                        bool unpack, hipStream_t s);
 hipError_t launch_attn_fwd(const AttnArgs &a, int D, int grid, hipStream_t s);
-hipError_t launch_attn_bwd_delta(const AttnArgs &a, int D, hipStream_t s);
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s);
 

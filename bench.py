@@ -207,9 +207,7 @@ def main() -> int:
     def step():
         plan = shared_plan if args.reuse_plan else fx.Plan(ctx, cu, Hq, Hkv, D, True)
         if not args.attention_only:
-            fx.flexsp_pack(ctx, xq, sq, P, stream)
-            fx.flexsp_pack(ctx, xk, sk, P, stream)
-            fx.flexsp_pack(ctx, xv, sv, P, stream)
+            fx.flexsp_pack_many(ctx, [xq, xk, xv], [sq, sk, sv], P, stream)    # q, k, v in one launch
         fx.flexsp_attn_varlen_fwd(ctx, plan, v3(sq), v3(sk), v3(sv), cud, v3(so), lse, stream=stream)
         if not args.attention_only:
             fx.flexsp_unpack(ctx, so, yo, stream)
@@ -217,9 +215,7 @@ def main() -> int:
         fx.flexsp_attn_varlen_bwd(ctx, plan, v3(sq), v3(sk), v3(sv), v3(so), v3(sg), lse, cud,
                                   v3(sdq), v3(sdk), v3(sdv), stream=stream)
         if not args.attention_only:
-            fx.flexsp_unpack(ctx, sdq, ydq, stream)
-            fx.flexsp_unpack(ctx, sdk, ydk, stream)
-            fx.flexsp_unpack(ctx, sdv, ydv, stream)
+            fx.flexsp_unpack_many(ctx, [sdq, sdk, sdv], [ydq, ydk, ydv], stream)  # dq, dk, dv in one launch
         return plan
 
     if args.attention_only:      # the slabs must hold data even when the permutes are skipped
@@ -271,7 +267,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "tokens": T, "sequences": len(lens), "max_len": max(lens),
                    "hq": Hq, "hkv": Hkv, "head_dim": D, "causal": True, "sp_degree": P,
-                   "step": ("" if args.reuse_plan else "plan+") + ("fwd+bwd" if args.attention_only else "4 pack+fwd+bwd+4 unpack"),
+                   "step": ("" if args.reuse_plan else "plan+") + ("fwd+bwd" if args.attention_only else "pack(q,k,v)+fwd+unpack(o)+pack(dO)+bwd+unpack(dq,dk,dv)"),
                    "flops_fwd_bwd": f_fwd + f_bwd, "seed": cfg.seed},
         "frac_of_bf16_mfma_peak": tflops * 1e12 / BF16_MFMA_PEAK,
         "attention_kernels_only": {"ms": attn_ms, "tflops": (f_fwd + f_bwd) / (attn_ms * 1e-3) / 1e12,

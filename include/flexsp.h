@@ -132,6 +132,22 @@ int flexsp_unpack(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_
                   int32_t P, int32_t elem_bytes, flexsp_stream stream);
 
 /*
+ * The same permutes for up to FLEXSP_PACK_MANY_MAX tensors in ONE launch: the q, k, v slabs on
+ * the way in (Eq. 2), the dq, dk, dv slabs on the way back.  Tensor i is [T, H[i], D] (the
+ * head counts may differ: grouped-query K and V have fewer heads than Q); T, D, P and
+ * elem_bytes are shared.  src, dst and H are HOST arrays of n entries (read before the call
+ * returns); src[i] / dst[i] are device pointers with the requirements of flexsp_pack, and no
+ * two of the 2n buffers may overlap.  Falls back to one launch per tensor when a tensor does
+ * not qualify for 16-byte accesses or has 2^31 or more of them.  n == 0 or T == 0 is a no-op.
+ * Errors: as flexsp_pack.
+ */
+#define FLEXSP_PACK_MANY_MAX 4
+int flexsp_pack_many(flexsp_ctx *ctx, int32_t n, const void *const *src, void *const *dst, int64_t T,
+                     const int32_t *H, int32_t D, int32_t P, int32_t elem_bytes, flexsp_stream stream);
+int flexsp_unpack_many(flexsp_ctx *ctx, int32_t n, const void *const *src, void *const *dst, int64_t T,
+                       const int32_t *H, int32_t D, int32_t P, int32_t elem_bytes, flexsp_stream stream);
+
+/*
  * Strided view of a [T, heads, D] bf16 tensor in device memory: element (t, h, d) lives at
  * ptr + (t*stride_token + h*stride_head + d) elements.  The last dim is contiguous, ptr and
  * both strides (in elements) must keep every row 16-byte aligned (multiples of 8 elements);

@@ -24,7 +24,8 @@ EXPORTS = (
     "flexsp_ctx_create", "flexsp_ctx_destroy", "flexsp_ctx_num_cu", "flexsp_ctx_num_xcd",
     "flexsp_plan_create", "flexsp_plan_destroy", "flexsp_plan_num_items", "flexsp_plan_get_items",
     "flexsp_plan_tile_rows", "flexsp_attn_bwd_workspace_bytes",
-    "flexsp_pack", "flexsp_unpack", "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd",
+    "flexsp_pack", "flexsp_unpack", "flexsp_pack_many", "flexsp_unpack_many",
+    "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd",
     "flexsp_profile_start", "flexsp_profile_stop",
 )
 KERNELS = ("pack", "unpack", "fwd", "bwd_delta", "bwd_dkv", "bwd_dq")
@@ -88,6 +89,10 @@ def lib() -> ctypes.CDLL:
         perm = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32, c_int32, c_void_p]
         L.flexsp_pack.argtypes = perm
         L.flexsp_unpack.argtypes = perm
+        many = [c_void_p, c_int32, POINTER(c_void_p), POINTER(c_void_p), c_int64, POINTER(c_int32), c_int32,
+                c_int32, c_int32, c_void_p]
+        L.flexsp_pack_many.argtypes = many
+        L.flexsp_unpack_many.argtypes = many
         L.flexsp_attn_varlen_fwd.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, c_void_p, c_int32,
                                              c_int32, c_int32, c_int32, c_int, c_float, Tensor, c_void_p,
                                              c_void_p]
@@ -219,6 +224,33 @@ def flexsp_unpack(ctx: Context, src, dst, stream=None):
     assert src.is_contiguous() and dst.is_contiguous() and dst.numel() == src.numel()
     _check(lib().flexsp_unpack(ctx.handle, src.data_ptr(), dst.data_ptr(), T, P * Hp, D, P,
                                src.element_size(), _stream(stream)), "flexsp_unpack")
+
+
+def _many(fn, name, ctx, srcs, dsts, T, heads, D, P, stream):
+    n = len(srcs)
+    assert n == len(dsts) and all(s.is_contiguous() and d.is_contiguous() and s.numel() == d.numel()
+                                  for s, d in zip(srcs, dsts))
+    eb = srcs[0].element_size()
+    assert all(s.element_size() == eb for s in srcs)
+    sp = (c_void_p * n)(*[s.data_ptr() for s in srcs])
+    dp = (c_void_p * n)(*[d.data_ptr() for d in dsts])
+    hh = (c_int32 * n)(*heads)
+    _check(fn(ctx.handle, n, sp, dp, T, hh, D, P, eb, _stream(stream)), name)
+
+
+def flexsp_pack_many(ctx: Context, srcs, dsts, P: int, stream=None):
+    """Several src [T,H_i,D] -> dst [P,T,H_i/P,D] in one launch (same T, D, element size)."""
+    T, _, D = srcs[0].shape
+    assert all(s.shape[0] == T and s.shape[2] == D for s in srcs)
+    _many(lib().flexsp_pack_many, "flexsp_pack_many", ctx, srcs, dsts, T, [s.shape[1] for s in srcs], D, P, stream)
+
+
+def flexsp_unpack_many(ctx: Context, srcs, dsts, stream=None):
+    """Several src [P,T,Hp_i,D] -> dst [T,P*Hp_i,D] in one launch."""
+    P, T, _, D = srcs[0].shape
+    assert all(s.shape[0] == P and s.shape[1] == T and s.shape[3] == D for s in srcs)
+    _many(lib().flexsp_unpack_many, "flexsp_unpack_many", ctx, srcs, dsts, T, [P * s.shape[2] for s in srcs], D, P,
+          stream)
 
 
 def flexsp_attn_varlen_fwd(ctx: Context, plan: Plan, q, k, v, cu_seqlens_dev, o, lse, *, head_begin=0,

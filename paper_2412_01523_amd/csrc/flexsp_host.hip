@@ -480,6 +480,52 @@ static int permute_entry(flexsp_ctx *ctx, const void *src, void *dst, int64_t T,
     return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
 }
 
+static int permute_many_entry(flexsp_ctx *ctx, int32_t n, const void *const *src, void *const *dst, int64_t T,
+                              const int32_t *H, int32_t D, int32_t P, int32_t eb, flexsp_stream stream, bool unpack)
+{
+    if (n < 0 || n > FLEXSP_PACK_MANY_MAX || (n > 0 && (!src || !dst || !H))) return FLEXSP_INVALID_ARGUMENT;
+    if (T < 0 || D <= 0 || P <= 0 || eb <= 0) return FLEXSP_INVALID_ARGUMENT;
+    if (eb != 1 && eb != 2 && eb != 4 && eb != 8 && eb != 16) return FLEXSP_UNSUPPORTED;
+    if (!ctx) return FLEXSP_INVALID_ARGUMENT;
+    for (int i = 0; i < n; i++)
+        if (H[i] <= 0 || H[i] % P != 0) return FLEXSP_INVALID_ARGUMENT;
+    if (T == 0 || n == 0) return FLEXSP_OK;
+    // every source against every destination: none may overlap
+    for (int i = 0; i < n; i++) {
+        if (!src[i] || !dst[i]) return FLEXSP_INVALID_ARGUMENT;
+        if (((uintptr_t)src[i] | (uintptr_t)dst[i]) % (uintptr_t)eb) return FLEXSP_INVALID_ARGUMENT;
+    }
+    for (int i = 0; i < n; i++)
+        for (int j = 0; j < n; j++) {
+            const char *s = (const char *)src[i], *d = (const char *)dst[j];
+            const int64_t sb = T * H[i] * D * eb, db = T * H[j] * D * eb;
+            if (s < d + db && d < s + sb) return FLEXSP_INVALID_ARGUMENT;
+            if (i < j) {
+                const char *d2 = (const char *)dst[i];
+                if (d2 < d + db && d < d2 + sb) return FLEXSP_INVALID_ARGUMENT;  // two destinations overlap
+            }
+        }
+    if (ctx->device < 0) return FLEXSP_NO_DEVICE;
+    hipError_t e;
+    {
+        Timed tm(ctx, unpack ? FLEXSP_K_UNPACK : FLEXSP_K_PACK, (hipStream_t)stream);
+        e = launch_pack_many(n, src, dst, T, H, D, P, eb, unpack, (hipStream_t)stream);
+    }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
+int flexsp_pack_many(flexsp_ctx *ctx, int32_t n, const void *const *src, void *const *dst, int64_t T,
+                     const int32_t *H, int32_t D, int32_t P, int32_t eb, flexsp_stream stream)
+{
+    return permute_many_entry(ctx, n, src, dst, T, H, D, P, eb, stream, false);
+}
+
+int flexsp_unpack_many(flexsp_ctx *ctx, int32_t n, const void *const *src, void *const *dst, int64_t T,
+                       const int32_t *H, int32_t D, int32_t P, int32_t eb, flexsp_stream stream)
+{
+    return permute_many_entry(ctx, n, src, dst, T, H, D, P, eb, stream, true);
+}
+
 int flexsp_pack(flexsp_ctx *ctx, const void *src, void *dst, int64_t T, int32_t H, int32_t D, int32_t P,
                 int32_t eb, flexsp_stream stream)
 {

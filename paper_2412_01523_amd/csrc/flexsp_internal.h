@@ -50,6 +50,8 @@ struct AttnArgs {
 // Launchers implemented next to their kernels.  All are asynchronous on `s`.
 hipError_t launch_pack(const void *src, void *dst, int64_t T, int H, int D, int P, int eb,
                        bool unpack, hipStream_t s);
+hipError_t launch_pack_many(int n, const void *const *src, void *const *dst, int64_t T, const int32_t *H, int D,
+                            int P, int eb, bool unpack, hipStream_t s);
 hipError_t launch_attn_fwd(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s);

@@ -22,6 +22,7 @@ template <> struct VecOf<2> { typedef uint16_t type; };
 template <> struct VecOf<1> { typedef uint8_t type; };
 
 constexpr int kPackThreads = 256;
+constexpr int kPackMany = 4;  // tensors per launch of the multi-tensor form
 
 // Units are vectors of VB bytes.  rc = vectors per (token, slab) run, row = vectors per
 // token on the sequence-sharded side (= P * rc), slab = T * rc vectors per slab.  One vector
@@ -55,6 +56,56 @@ __global__ __launch_bounds__(kPackThreads) void permute_kernel(
         __builtin_nontemporal_store(__builtin_nontemporal_load(&src[o]), &dst[c]);
     else
         __builtin_nontemporal_store(__builtin_nontemporal_load(&src[c]), &dst[o]);
+}
+
+// Several tensors in one launch (blockIdx.y picks the tensor): the same walk, 16-byte vectors and
+// 32-bit indices only.  Saves the launches in between and lets one tensor's last workgroups
+// overlap the next one's first.
+struct ManyArgs {
+    const u32x4 *src[kPackMany];
+    u32x4 *dst[kPackMany];
+    uint32_t total[kPackMany], slab[kPackMany], row[kPackMany], rc[kPackMany];
+    int row_shift[kPackMany], rc_shift[kPackMany];
+};
+// (the tensor index is resolved by a chain of compile-time cases: indexing the by-value argument
+// arrays with a run-time value would move them to scratch memory)
+template <bool UNPACK, int Y>
+__device__ __forceinline__ void permute_one_of_many(const ManyArgs &m, uint32_t c)
+{
+    if (c >= m.total[Y]) return;
+    const uint32_t row = m.row[Y], rc = m.rc[Y];
+    uint32_t t, e, r, w;
+    if (m.row_shift[Y] >= 0) {
+        t = c >> m.row_shift[Y];
+        e = c & (row - 1);
+    } else {
+        t = c / row;
+        e = c - t * row;
+    }
+    if (m.rc_shift[Y] >= 0) {
+        r = e >> m.rc_shift[Y];
+        w = e & (rc - 1);
+    } else {
+        r = e / rc;
+        w = e - r * rc;
+    }
+    const uint32_t o = r * m.slab[Y] + t * rc + w;
+    if (UNPACK)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(&m.src[Y][o]), &m.dst[Y][c]);
+    else
+        __builtin_nontemporal_store(__builtin_nontemporal_load(&m.src[Y][c]), &m.dst[Y][o]);
+}
+template <bool UNPACK>
+__global__ __launch_bounds__(kPackThreads) void permute_many_kernel(const ManyArgs m)
+{
+    static_assert(kPackMany == 4, "one case per tensor below");
+    const uint32_t c = blockIdx.x * kPackThreads + threadIdx.x;
+    switch (blockIdx.y) {
+    case 0: permute_one_of_many<UNPACK, 0>(m, c); break;
+    case 1: permute_one_of_many<UNPACK, 1>(m, c); break;
+    case 2: permute_one_of_many<UNPACK, 2>(m, c); break;
+    default: permute_one_of_many<UNPACK, 3>(m, c); break;
+    }
 }
 
 inline int shift_of(int64_t x)
@@ -109,6 +160,53 @@ hipError_t launch_pack(const void *src, void *dst, int64_t T, int H, int D, int 
     if ((bits & 3) == 0) return launch_vb<4>(src, dst, bytes, T, run_bytes, P, unpack, s);
     if ((bits & 1) == 0) return launch_vb<2>(src, dst, bytes, T, run_bytes, P, unpack, s);
     return launch_vb<1>(src, dst, bytes, T, run_bytes, P, unpack, s);
+}
+
+// n tensors [T, H[i], D] with the same T, D, P and element size.  One launch when every tensor
+// qualifies for 16-byte vectors and 32-bit indices, otherwise one launch per tensor.
+hipError_t launch_pack_many(int n, const void *const *src, void *const *dst, int64_t T, const int32_t *H, int D,
+                            int P, int eb, bool unpack, hipStream_t s)
+{
+    ManyArgs m;
+    bool fast = n <= kPackMany;
+    int64_t most = 0;
+    for (int i = 0; i < n && fast; i++) {
+        const int64_t run_bytes = (int64_t)(H[i] / P) * D * eb, bytes = T * P * run_bytes;
+        const uintptr_t bits = (uintptr_t)src[i] | (uintptr_t)dst[i] | (uintptr_t)run_bytes;
+        const int64_t total = bytes / 16;
+        if ((bits & 15) != 0 || total + kPackThreads >= ((int64_t)1 << 31)) {
+            fast = false;
+            break;
+        }
+        const int64_t rc = run_bytes / 16;
+        m.src[i] = (const u32x4 *)src[i];
+        m.dst[i] = (u32x4 *)dst[i];
+        m.total[i] = (uint32_t)total;
+        m.rc[i] = (uint32_t)rc;
+        m.slab[i] = (uint32_t)(T * rc);
+        m.row[i] = (uint32_t)((int64_t)P * rc);
+        m.row_shift[i] = shift_of((int64_t)P * rc);
+        m.rc_shift[i] = shift_of(rc);
+        most = total > most ? total : most;
+    }
+    if (!fast) {
+        for (int i = 0; i < n; i++) {
+            hipError_t e = launch_pack(src[i], dst[i], T, H[i], D, P, eb, unpack, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    if (most == 0) return hipSuccess;
+    for (int i = n; i < kPackMany; i++) {
+        m.src[i] = nullptr; m.dst[i] = nullptr;
+        m.total[i] = 0; m.slab[i] = 0; m.row[i] = 1; m.rc[i] = 1; m.row_shift[i] = 0; m.rc_shift[i] = 0;
+    }
+    const dim3 grid((unsigned)((most + kPackThreads - 1) / kPackThreads), (unsigned)n);
+    if (unpack)
+        hipLaunchKernelGGL(permute_many_kernel<true>, grid, dim3(kPackThreads), 0, s, m);
+    else
+        hipLaunchKernelGGL(permute_many_kernel<false>, grid, dim3(kPackThreads), 0, s, m);
+    return hipGetLastError();
 }
 
 }  // namespace flexsp

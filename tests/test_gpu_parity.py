@@ -66,6 +66,34 @@ def test_pack_unpack_bit_exact(ctx, T, H, D, P, dt):
     assert np.array_equal(oracle.unpack(want), x)
 
 
+MANY_CASES = [
+    # T, heads of each tensor, D, P
+    (1000, (32, 32, 32), 128, 8),        # q, k, v of equal shape: one launch
+    (777, (16, 2, 2, 16), 128, 2),       # grouped-query: k and v have fewer heads
+    (333, (4, 4), 5, 2),                 # run = 20 B: falls back to one launch per tensor
+    (0, (4, 4, 4), 8, 2),                # empty
+    (129, (8,), 64, 4),                  # a single tensor
+]
+
+
+@pytest.mark.parametrize("T,heads,D,P", MANY_CASES)
+def test_pack_many_unpack_many_bit_exact(ctx, T, heads, D, P):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    say(f"multi-tensor permute case T={T} heads={heads} D={D} P={P}")
+    rng = np.random.Generator(np.random.Philox(key=[78, T + len(heads)]))
+    xs = [rng.integers(0, 65535, size=T * H * D, dtype=np.uint16, endpoint=True).reshape(T, H, D) for H in heads]
+    xd = [torch.from_numpy(x.view(np.int16)).cuda() for x in xs]
+    yd = [torch.full((P, T, H // P, D), 0x55, dtype=torch.int16, device="cuda") for H in heads]
+    fx.flexsp_pack_many(ctx, xd, yd, P)
+    for x, y in zip(xs, yd):
+        assert np.array_equal(y.cpu().numpy().view(np.uint16), oracle.pack(x, P))
+    zd = [torch.full((T, H, D), 0x33, dtype=torch.int16, device="cuda") for H in heads]
+    fx.flexsp_unpack_many(ctx, yd, zd)
+    for x, z in zip(xs, zd):
+        assert np.array_equal(z.cpu().numpy().view(np.uint16), x)
+
+
 def test_pack_misaligned_base_uses_narrow_path(ctx):
     import torch
     from paper_2412_01523_amd import binding as fx

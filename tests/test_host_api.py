@@ -146,6 +146,19 @@ def test_permute_and_attention_validation_without_a_device(host_ctx):
     assert L.flexsp_unpack(h, a, a + 2048, 0, 4, 8, 2, 2, None) == fx.OK                # empty: no-op
     # well-formed call on a host-only context: refuses to launch, does not crash
     assert L.flexsp_pack(h, a, a + 2048, 4, 4, 8, 2, 2, None) == fx.NO_DEVICE
+    # the multi-tensor form: same checks per tensor, and no two of the 2n buffers may overlap
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    def many(fn, srcs, dsts, heads, T=4, D=8, P=2, eb=2, n=None):
+        n = len(srcs) if n is None else n
+        return fn(h, n, (vp * len(srcs))(*srcs), (vp * len(dsts))(*dsts), T, (i32 * len(heads))(*heads), D, P, eb, None)
+    assert many(L.flexsp_pack_many, [a, a + 512], [a + 1024, a + 1536], [4, 4]) == fx.NO_DEVICE
+    assert many(L.flexsp_pack_many, [a, a + 512], [a + 1024, a + 1536], [4, 3]) == fx.INVALID_ARGUMENT   # H % P
+    assert many(L.flexsp_pack_many, [a, a + 512], [a + 1024, a + 1100], [4, 4]) == fx.INVALID_ARGUMENT   # dst/dst overlap
+    assert many(L.flexsp_pack_many, [a, a + 512], [a + 600, a + 1536], [4, 4]) == fx.INVALID_ARGUMENT    # src/dst overlap
+    assert many(L.flexsp_unpack_many, [a, None], [a + 1024, a + 1536], [4, 4]) == fx.INVALID_ARGUMENT    # null tensor
+    assert many(L.flexsp_unpack_many, [a] * 5, [a] * 5, [4] * 5) == fx.INVALID_ARGUMENT                  # too many
+    assert many(L.flexsp_unpack_many, [], [], [], n=0) == fx.OK                                          # none: no-op
+    assert many(L.flexsp_pack_many, [a, a + 512], [a + 1024, a + 1536], [4, 4], T=0) == fx.OK            # empty
     plan = fx.Plan(host_ctx, np.array([0, 8], dtype=np.int32), 2, 2, 64, True)
     t = fx.Tensor(a, 128, 64)
     bad = fx.Tensor(a + 2, 128, 64)                                                      # misaligned

@@ -216,32 +216,26 @@ def main() -> int:
                                   v3(sdq), v3(sdk), v3(sdv), stream=stream)
         if not args.attention_only:
             fx.flexsp_unpack_many(ctx, [sdq, sdk, sdv], [ydq, ydk, ydv], stream)  # dq, dk, dv in one launch
-        return plan
+        if plan is not shared_plan:
+            plan.close()    # hands the plan's memory back to the context (no synchronisation)
+        return None
 
     if args.attention_only:      # the slabs must hold data even when the permutes are skipped
         for x, s in ((xq, sq), (xk, sk), (xv, sv), (xg, sg)):
             fx.flexsp_pack(ctx, x, s, P, stream)
 
-    plans = []
     for _ in range(args.warmup):
-        plans.append(step())
+        step()
     torch.cuda.synchronize()
-    for p in plans:
-        if p is not shared_plan:
-            p.close()
-    plans = []
 
     ctx.profile_start(16 * max(args.steps, 1))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        plans.append(step())      # plans are released after the timed region (hipFree synchronises)
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = ctx.profile_stop()
-    for p in plans:
-        if p is not shared_plan:
-            p.close()
 
     ms_step = (t1 - t0) * 1e3 / max(args.steps, 1)
     tflops = (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12

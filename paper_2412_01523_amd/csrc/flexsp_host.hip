@@ -15,10 +15,26 @@ struct EventPair {
     int kernel;
 };
 
+// Device memory of a plan plus the pinned host buffer its queues are uploaded from.  Slabs are
+// recycled through the context: creating a plan per micro-batch then costs neither an allocation
+// nor a device-wide synchronisation (hipFree), and the upload is an asynchronous copy.
+struct PlanSlab {
+    void *dev = nullptr;
+    size_t dev_bytes = 0;
+    void *host = nullptr;  // pinned
+    size_t host_bytes = 0;
+    hipEvent_t ready = nullptr;  // recorded on the upload stream after the copy
+    hipEvent_t done = nullptr;   // recorded on the last stream that ran kernels on this slab
+    bool done_valid = false;
+};
+constexpr size_t kSlabPoolMax = 8;
+
 struct flexsp_ctx {
     int device;  // -1: host-only
     int num_cu;
     int num_xcd;
+    hipStream_t upload = nullptr;  // non-blocking stream (default priority) for plan uploads
+    std::vector<PlanSlab> slabs;   // free slabs
     // profiling: a pool of event pairs created by flexsp_profile_start
     bool profiling;
     std::vector<EventPair> events;
@@ -41,6 +57,10 @@ struct flexsp_plan {
     // device side (null for host-only plans): one allocation, carved up
     void *dev_base;
     size_t dev_bytes;
+    PlanSlab slab;
+    bool uploaded;            // the upload is known to have completed
+    bool used, multi_stream;  // kernels were launched on this plan; on more than one stream
+    hipStream_t last_stream;
     PassQueues dq[3];
     float *delta;
     size_t delta_bytes;
@@ -57,6 +77,68 @@ int hip_fail(hipError_t e)
 }
 
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+void slab_free(PlanSlab &s)
+{
+    if (s.dev) (void)hipFree(s.dev);
+    if (s.host) (void)hipHostFree(s.host);
+    if (s.ready) (void)hipEventDestroy(s.ready);
+    if (s.done) (void)hipEventDestroy(s.done);
+    s = PlanSlab();
+}
+
+// A slab with at least the given sizes: the smallest adequate one from the pool, else a new one
+// (a quarter larger than asked, so that the next, slightly different batch fits too).
+hipError_t slab_get(flexsp_ctx *ctx, size_t dev_bytes, size_t host_bytes, PlanSlab &out)
+{
+    int best = -1;
+    for (size_t i = 0; i < ctx->slabs.size(); i++) {
+        const PlanSlab &s = ctx->slabs[i];
+        if (s.dev_bytes >= dev_bytes && s.host_bytes >= host_bytes &&
+            (best < 0 || s.dev_bytes < ctx->slabs[best].dev_bytes))
+            best = (int)i;
+    }
+    if (best >= 0) {
+        out = ctx->slabs[best];
+        ctx->slabs.erase(ctx->slabs.begin() + best);
+        // the previous upload from this pinned buffer must be over before the host refills it
+        return hipEventSynchronize(out.ready);
+    }
+    PlanSlab s;
+    s.dev_bytes = dev_bytes + dev_bytes / 4 + 256;
+    s.host_bytes = host_bytes + host_bytes / 4 + 256;
+    hipError_t e = hipMalloc(&s.dev, s.dev_bytes);
+    if (e == hipSuccess) e = hipHostMalloc(&s.host, s.host_bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s.ready, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        slab_free(s);
+        return e;
+    }
+    out = s;
+    return hipSuccess;
+}
+
+// Called by the hot entry points before they launch on `stream`: the kernels must see the
+// uploaded queues.  Once the upload is known to be complete this is one flag test.
+hipError_t plan_before_launch(flexsp_plan *plan, hipStream_t stream)
+{
+    if (!plan->uploaded) {
+        hipError_t q = hipEventQuery(plan->slab.ready);
+        if (q == hipSuccess) {
+            plan->uploaded = true;
+        } else if (q == hipErrorNotReady) {
+            hipError_t e = hipStreamWaitEvent(stream, plan->slab.ready, 0);
+            if (e != hipSuccess) return e;
+        } else {
+            return q;
+        }
+    }
+    if (plan->used && plan->last_stream != stream) plan->multi_stream = true;
+    plan->used = true;
+    plan->last_stream = stream;
+    return hipSuccess;
+}
 
 // Brackets one kernel launch with a pair of events while profiling is on.
 struct Timed {
@@ -276,6 +358,12 @@ int flexsp_ctx_create(flexsp_ctx **out, int device)
             return FLEXSP_NO_DEVICE;
         }
         c->num_cu = pr.multiProcessorCount;
+        e = hipSetDevice(device);
+        if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking);
+        if (e != hipSuccess) {
+            delete c;
+            return hip_fail(e);
+        }
     }
     *out = c;
     return FLEXSP_OK;
@@ -287,6 +375,12 @@ void flexsp_ctx_destroy(flexsp_ctx *ctx)
     for (EventPair &e : ctx->events) {
         (void)hipEventDestroy(e.start);
         (void)hipEventDestroy(e.stop);
+    }
+    if (ctx->device >= 0) {
+        (void)hipSetDevice(ctx->device);
+        if (!ctx->slabs.empty()) (void)hipDeviceSynchronize();  // kernels of destroyed plans may still run
+        for (PlanSlab &s : ctx->slabs) slab_free(s);
+        if (ctx->upload) (void)hipStreamDestroy(ctx->upload);
     }
     delete ctx;
 }
@@ -359,6 +453,7 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
     p->B = B; p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->causal = causal ? 1 : 0;
     p->T = cu[B];
     p->dev_base = nullptr; p->dev_bytes = 0; p->delta = nullptr;
+    p->uploaded = false; p->used = false; p->multi_stream = false; p->last_stream = nullptr;
     p->delta_bytes = 2 * (size_t)p->T * Hq * sizeof(float);  // delta and log2-domain LSE, [Hq, T] each
     try {
         p->cu.assign(cu, cu + B + 1);
@@ -392,32 +487,39 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
         size_t delta_off = off;
         off = align(off + p->delta_bytes + 512);  // the dK/dV kernel reads up to 63 floats past a row's end
         hipError_t e = hipSetDevice(ctx->device);
-        if (e == hipSuccess) e = hipMalloc(&p->dev_base, off ? off : 256);
+        if (e == hipSuccess) e = slab_get(ctx, off ? off : 256, head_bytes ? head_bytes : 256, p->slab);
         if (e != hipSuccess) {
             delete p;
             return hip_fail(e);
         }
+        p->dev_base = p->slab.dev;
         p->dev_bytes = off;
-        std::vector<char> stage(head_bytes, 0);
+        char *stage = (char *)p->slab.host;
+        std::memset(stage, 0, head_bytes);  // also the ticket counters: every plan starts with them clear
         for (int i = 0; i < 3; i++) {
             if (!p->pass[i].items.empty())
-                std::memcpy(stage.data() + item_off[i], p->pass[i].items.data(),
+                std::memcpy(stage + item_off[i], p->pass[i].items.data(),
                             p->pass[i].items.size() * sizeof(flexsp_item));
-            int32_t *o = (int32_t *)(stage.data() + offs_off[i]);
+            int32_t *o = (int32_t *)(stage + offs_off[i]);
             for (int x = 0; x <= nq; x++) o[x] = (int32_t)p->pass[i].offsets[x];
             p->dq[i].items = (const flexsp_item *)((char *)p->dev_base + item_off[i]);
             p->dq[i].offsets = (const int32_t *)((char *)p->dev_base + offs_off[i]);
             p->dq[i].counters = (int32_t *)((char *)p->dev_base + ctr_off[i]);
             p->dq[i].nq = nq;
         }
-        if (head_bytes) {
-            e = hipMemcpy(p->dev_base, stage.data(), head_bytes, hipMemcpyHostToDevice);
-            if (e != hipSuccess) {
-                (void)hipFree(p->dev_base);
-                delete p;
-                return hip_fail(e);
-            }
+        // asynchronous upload on the context's own stream, after the kernels of the slab's previous
+        // plan; the hot calls make their stream wait for `ready` (or find it complete already)
+        if (p->slab.done_valid) e = hipStreamWaitEvent(ctx->upload, p->slab.done, 0);
+        if (e == hipSuccess && head_bytes)
+            e = hipMemcpyAsync(p->dev_base, stage, head_bytes, hipMemcpyHostToDevice, ctx->upload);
+        if (e == hipSuccess) e = hipEventRecord(p->slab.ready, ctx->upload);
+        if (e != hipSuccess) {
+            (void)hipStreamSynchronize(ctx->upload);
+            slab_free(p->slab);
+            delete p;
+            return hip_fail(e);
         }
+        p->slab.done_valid = false;
         p->delta = (float *)((char *)p->dev_base + delta_off);
     }
     *out = p;
@@ -427,7 +529,32 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
 void flexsp_plan_destroy(flexsp_plan *plan)
 {
     if (!plan) return;
-    if (plan->dev_base) (void)hipFree(plan->dev_base);
+    if (plan->dev_base) {
+        flexsp_ctx *ctx = plan->ctx;
+        (void)hipSetDevice(ctx->device);
+        PlanSlab s = plan->slab;
+        // whoever gets this slab next must come after the kernels still running on it
+        s.done_valid = false;
+        if (plan->used) {
+            if (plan->multi_stream || hipEventRecord(s.done, plan->last_stream) != hipSuccess)
+                (void)hipDeviceSynchronize();
+            else
+                s.done_valid = true;
+        }
+        if (ctx->slabs.size() < kSlabPoolMax) {
+            try {
+                ctx->slabs.push_back(s);
+            } catch (const std::bad_alloc &) {
+                if (s.done_valid) (void)hipEventSynchronize(s.done);
+                (void)hipEventSynchronize(s.ready);
+                slab_free(s);
+            }
+        } else {
+            if (s.done_valid) (void)hipEventSynchronize(s.done);
+            (void)hipEventSynchronize(s.ready);
+            slab_free(s);
+        }
+    }
     delete plan;
 }
 
@@ -553,6 +680,10 @@ int flexsp_attn_varlen_fwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
     if (!view_ok(q) || !view_ok(k) || !view_ok(v) || !view_ok(o) || !lse) return FLEXSP_INVALID_ARGUMENT;
     if (!std::isfinite(scale)) return FLEXSP_INVALID_ARGUMENT;
     if (plan->pass[FLEXSP_PASS_FWD].items.empty()) return FLEXSP_OK;
+    {
+        hipError_t pe = plan_before_launch(plan, (hipStream_t)stream);
+        if (pe != hipSuccess) return hip_fail(pe);
+    }
     if (scale <= 0.f) scale = 1.0f / std::sqrt((float)plan->D);
     AttnArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -592,6 +723,10 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
     if (rc) return rc;
     if (!views || !std::isfinite(scale)) return FLEXSP_INVALID_ARGUMENT;
     if (plan->pass[FLEXSP_PASS_FWD].items.empty()) return FLEXSP_OK;
+    {
+        hipError_t pe = plan_before_launch(plan, (hipStream_t)stream);
+        if (pe != hipSuccess) return hip_fail(pe);
+    }
     if (scale <= 0.f) scale = 1.0f / std::sqrt((float)plan->D);
     AttnArgs a;
     std::memset(&a, 0, sizeof(a));

@@ -196,6 +196,47 @@ def test_explicit_scale_and_plan_reuse_and_determinism(ctx):
     plan.close()
 
 
+def test_plan_per_step_recycles_memory_in_stream_order(ctx):
+    """A plan per micro-batch, destroyed while its kernels may still run: the context hands the
+    memory to the next plan only after them (nothing synchronises in between), so every step must
+    reproduce the bits of a run with a long-lived plan."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    Hq, Hkv, D = 4, 4, 128
+    batches = [[1500, 300, 1000, 64], [2048, 7, 500], [900] * 3]      # different item counts and sizes
+    data, want = [], []
+    for i, lens in enumerate(batches):
+        T = sum(lens)
+        cu = wl.cu_seqlens(lens)
+        q, k, v, g = (to_dev(wl.normal_bf16(500 + i, j, (T, Hq, D))) for j in range(4))
+        bufs = [torch.zeros((T, Hq, D), dtype=torch.bfloat16, device="cuda") for _ in range(4)]
+        lse = torch.zeros((Hq, T), dtype=torch.float32, device="cuda")
+        data.append((cu, torch.from_numpy(cu).cuda(), q, k, v, g, bufs, lse))
+
+    def run(i, plan):
+        cu, cud, q, k, v, g, (o, gq, gk, gv), lse = data[i]
+        fx.flexsp_attn_varlen_fwd(ctx, plan, q, k, v, cud, o, lse)
+        fx.flexsp_attn_varlen_bwd(ctx, plan, q, k, v, o, g, lse, cud, gq, gk, gv)
+
+    for i in range(len(batches)):                                      # reference: long-lived plans
+        plan = fx.Plan(ctx, data[i][0], Hq, Hkv, D, True)
+        run(i, plan)
+        torch.cuda.synchronize()
+        want.append([to_bits(x).copy() for x in data[i][6]])
+        plan.close()
+    for step in range(24):                                             # more steps than pooled buffers
+        i = step % len(batches)
+        for x in data[i][6]:
+            x.zero_()
+        plan = fx.Plan(ctx, data[i][0], Hq, Hkv, D, True)
+        run(i, plan)
+        plan.close()                                                   # no synchronisation here
+        if step % 5 == 4 or step >= 21:
+            torch.cuda.synchronize()
+            for got, ref in zip(data[i][6], want[i]):
+                assert np.array_equal(to_bits(got), ref), f"step {step}"
+
+
 def test_heads_subset_of_a_strided_tensor(ctx):
     """q/k/v/o given as views into the sequence-sharded [T, H_tot, D] tensors: heads 8..11 of 16."""
     import torch

@@ -208,6 +208,38 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
                            flexsp_tensor dv, int32_t grad_dtype, flexsp_stream stream);
 
 /*
+ * ---------------------------------------------------------------------------------------------
+ * Planner pieces that are exact and need no external solver (host only, no GPU involved).
+ * All lengths are token counts, 0 <= s <= 2^40; arrays are host pointers.
+ *
+ * flexsp_bucket_dp - adaptive sequence bucketing (Sec. 4.1.3 "Problem Solving", the bucketing
+ *   objective and its dynamic programme).  Groups K sequence lengths (any order) into at most Q
+ *   buckets, bucket q holding the lengths in (limit[q-1], limit[q]], such that the total
+ *   deviation sum_k (limit[bucket(k)] - s_k) is minimal.
+ *     limits       out, capacity Q: the buckets' upper limits, ascending (each is one of the lengths)
+ *     num_buckets  out: how many limits were written (< Q when fewer distinct lengths exist)
+ *     bucket_of    out, K entries, or NULL: bucket index of every input length
+ *     error        out: the minimal total deviation
+ *
+ * flexsp_chunk_dp - memory-balanced micro-batch chunking (Appendix A, the min-max objective and
+ *   its dynamic programme).  Splits the K lengths, IN THE GIVEN ORDER, into M consecutive,
+ *   non-empty micro-batches so that the largest micro-batch token count is minimal (1 <= M <= K).
+ *     ends         out, M entries: ends[i] = index one past the last sequence of micro-batch i
+ *                  (ends[M-1] = K).  When several splits are optimal, one of them.
+ *     max_tokens   out: the minimal possible largest micro-batch token count
+ *
+ * flexsp_min_microbatches - smallest feasible micro-batch count (Sec. 4.2, takeaway #1):
+ *   ceil(batch_tokens / cluster_token_capacity); negative status for invalid arguments.
+ *
+ * Errors: INVALID_ARGUMENT (null pointers, negative or oversized lengths, Q <= 0, M outside
+ * 1..K), UNSUPPORTED (K >= 2^31), OUT_OF_MEMORY.
+ */
+int flexsp_bucket_dp(const int64_t *lens, int64_t K, int32_t Q, int64_t *limits, int32_t *num_buckets,
+                     int32_t *bucket_of, int64_t *error);
+int flexsp_chunk_dp(const int64_t *lens, int64_t K, int32_t M, int64_t *ends, int64_t *max_tokens);
+int64_t flexsp_min_microbatches(int64_t batch_tokens, int64_t cluster_token_capacity);
+
+/*
  * Per-kernel timing for benchmarks.  Between flexsp_profile_start and flexsp_profile_stop every
  * kernel launched through `ctx` is bracketed by a pair of HIP events on the caller's stream.
  * flexsp_profile_stop waits for the recorded events (it synchronises the host), adds up the

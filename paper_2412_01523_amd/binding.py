@@ -27,6 +27,7 @@ EXPORTS = (
     "flexsp_pack", "flexsp_unpack", "flexsp_pack_many", "flexsp_unpack_many",
     "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd",
     "flexsp_profile_start", "flexsp_profile_stop",
+    "flexsp_bucket_dp", "flexsp_chunk_dp", "flexsp_min_microbatches",
 )
 KERNELS = ("pack", "unpack", "fwd", "bwd_delta", "bwd_dkv", "bwd_dq")
 
@@ -99,6 +100,11 @@ def lib() -> ctypes.CDLL:
         L.flexsp_attn_varlen_bwd.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, Tensor, Tensor,
                                              c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int,
                                              c_float, Tensor, Tensor, Tensor, c_int32, c_void_p]
+        L.flexsp_bucket_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int32), c_void_p,
+                                       POINTER(c_int64)]
+        L.flexsp_chunk_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int64)]
+        L.flexsp_min_microbatches.argtypes = [c_int64, c_int64]
+        L.flexsp_min_microbatches.restype = c_int64
         L.flexsp_profile_start.argtypes = [c_void_p, c_int32]
         L.flexsp_profile_stop.argtypes = [c_void_p, POINTER(Profile)]
         _lib = L
@@ -276,3 +282,31 @@ def flexsp_attn_varlen_bwd(ctx: Context, plan: Plan, q, k, v, o, dO, lse, cu_seq
                                         head_count, kv_head_begin, kv_head_count, int(bool(causal)),
                                         float(softmax_scale), _view(dq), _view(dk), _view(dv),
                                         grad_dtype, _stream(stream)), "flexsp_attn_varlen_bwd")
+
+
+# ----------------------------------------------------------------------------- planner pieces (host only)
+def flexsp_bucket_dp(lens, Q: int = 16):
+    """(limits, bucket_of, error): at most Q buckets with minimal total deviation from the upper limits."""
+    s = np.ascontiguousarray(lens, dtype=np.int64)
+    limits = np.zeros(max(Q, 1), dtype=np.int64)
+    bucket_of = np.zeros(len(s), dtype=np.int32)
+    nb, err = c_int32(0), c_int64(0)
+    _check(lib().flexsp_bucket_dp(s.ctypes.data, len(s), Q, limits.ctypes.data, byref(nb), bucket_of.ctypes.data,
+                                  byref(err)), "flexsp_bucket_dp")
+    return limits[:nb.value].copy(), bucket_of, int(err.value)
+
+
+def flexsp_chunk_dp(lens, M: int):
+    """(ends, max_tokens): M consecutive non-empty micro-batches with the smallest possible largest token count."""
+    s = np.ascontiguousarray(lens, dtype=np.int64)
+    ends = np.zeros(max(M, 1), dtype=np.int64)
+    mx = c_int64(0)
+    _check(lib().flexsp_chunk_dp(s.ctypes.data, len(s), M, ends.ctypes.data, byref(mx)), "flexsp_chunk_dp")
+    return ends[:M].copy(), int(mx.value)
+
+
+def flexsp_min_microbatches(batch_tokens: int, cluster_token_capacity: int) -> int:
+    r = lib().flexsp_min_microbatches(batch_tokens, cluster_token_capacity)
+    if r < 0:
+        raise FlexspError(int(r), "flexsp_min_microbatches")
+    return int(r)

@@ -3,12 +3,13 @@
 // log-sum-exp, and delta_i = dO_i . O_i:
 //     dV = P^T dO,   dP = dO V^T,   dS = P o (dP - delta),
 //     dQ = scale dS K,   dK = scale dS^T Q.
-// Three kernels, no floating-point atomics (results are deterministic):
-//   delta   one pass over dO and O (HBM-bound);
-//   dK/dV   one work item = 128 keys of one (sequence, kv head); loops over the query heads
-//           of the group and over the query rows that see those keys; dK^T, dV^T stay in
-//           registers, so grouped-query heads are summed without a reduction pass;
-//   dQ      one work item = 128 query rows of one (sequence, head); loops over key tiles.
+// Two kernels, no floating-point atomics (results are deterministic):
+//   dQ      runs first; one work item = 128 query rows of one (sequence, head); loops over key
+//           tiles; its prologue also computes delta and the base-2 log-sum-exp of its rows and
+//           leaves them in the plan's scratch for the second kernel;
+//   dK/dV   one work item = 64 keys of one (sequence, kv head); loops over the query heads of
+//           the group and over the query rows that see those keys; dK^T, dV^T stay in
+//           registers, so grouped-query heads are summed without a reduction pass.
 // The 32x32 accumulator keeps one COLUMN per lane, and only its ROW index can be contracted
 // in a following MFMA.  Hence dK/dV computes S = Q K^T (rows = queries) and dQ computes
 // S^T = K Q^T (rows = keys).  Operands whose contraction index runs along the rows of a

@@ -29,17 +29,22 @@ def errors(gpu_f64, ref_f64):
     return max_abs, rel
 
 
-def bf16_store_tol(ref_f64):
-    """max-abs tolerance for a result that is ROUNDED TO bf16 at the end: the stated 2e-2, or half
-    a bf16 ulp of the largest reference value (2^-8 relative) where that alone is larger, which
-    happens once |value| >= 5.12 (grouped-query sums of dK/dV reach that)."""
-    return max(MAX_ABS, 2.0 ** -8 * float(np.abs(ref_f64).max()))
+def bf16_store_tol(ref_f64, err_f32):
+    """Element-wise max-abs tolerance for a result that is ROUNDED TO bf16 at the end: the stated
+    2e-2, or, where that is larger, the error the same tensor showed when stored as fp32
+    (`err_f32`, itself held to 2e-2) plus half a bf16 ulp of the reference value (2^-8 relative).
+    The final rounding alone is 1.56e-2 once |value| >= 4, which grouped-query sums of dK/dV and
+    the dV rows of very short sequences (dV ~ a few dO rows, tails of N(0,1) beyond 4) reach."""
+    return np.maximum(MAX_ABS, err_f32 + 2.0 ** -8 * np.abs(ref_f64))
 
 
 def assert_close(name, gpu_f64, ref_f64, max_abs=MAX_ABS, rel_l2=REL_L2):
+    """max_abs: a scalar, or an array of per-element tolerances shaped like the tensors."""
     assert np.isfinite(gpu_f64).all(), f"{name}: non-finite values"
     ma, rl = errors(gpu_f64, ref_f64)
-    assert ma <= max_abs and rl <= rel_l2, f"{name}: max_abs={ma:.3e} (tol {max_abs}) rel_l2={rl:.3e} (tol {rel_l2})"
+    worst = float((np.abs(gpu_f64 - ref_f64) - max_abs).max()) if gpu_f64.size else -1.0
+    assert worst <= 0 and rl <= rel_l2, \
+        f"{name}: max_abs={ma:.3e}, {worst:.3e} beyond its tolerance (base {MAX_ABS}); rel_l2={rl:.3e} (tol {rel_l2})"
     return ma, rl
 
 

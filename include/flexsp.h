@@ -64,6 +64,10 @@ const char *flexsp_version(void);
  * FLEXSP_NO_DEVICE if it does not exist or is not gfx950.  device == -1 creates a
  * HOST-ONLY context: plans can be built and inspected with it (for tests of the host
  * logic), every launch through it fails with FLEXSP_NO_DEVICE.
+ * Creating or destroying a device context or one of its plans, and flexsp_profile_start,
+ * leave the context's device as the calling thread's current HIP device; the hot calls do
+ * not touch the current device (the stream they are given must belong to the context's
+ * device).  Destroy every plan before its context.
  */
 int flexsp_ctx_create(flexsp_ctx **out, int device);
 void flexsp_ctx_destroy(flexsp_ctx *ctx);

@@ -372,12 +372,12 @@ int flexsp_ctx_create(flexsp_ctx **out, int device)
 void flexsp_ctx_destroy(flexsp_ctx *ctx)
 {
     if (!ctx) return;
+    if (ctx->device >= 0) (void)hipSetDevice(ctx->device);
     for (EventPair &e : ctx->events) {
         (void)hipEventDestroy(e.start);
         (void)hipEventDestroy(e.stop);
     }
     if (ctx->device >= 0) {
-        (void)hipSetDevice(ctx->device);
         if (!ctx->slabs.empty()) (void)hipDeviceSynchronize();  // kernels of destroyed plans may still run
         for (PlanSlab &s : ctx->slabs) slab_free(s);
         if (ctx->upload) (void)hipStreamDestroy(ctx->upload);
@@ -393,6 +393,10 @@ int flexsp_profile_start(flexsp_ctx *ctx, int32_t max_launches)
         ctx->events.reserve((size_t)max_launches);
     } catch (const std::bad_alloc &) {
         return FLEXSP_OUT_OF_MEMORY;
+    }
+    {
+        hipError_t r = hipSetDevice(ctx->device);  // events belong to the device that is current when they are made
+        if (r != hipSuccess) return hip_fail(r);
     }
     while (ctx->events.size() < (size_t)max_launches) {
         EventPair e;

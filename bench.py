@@ -141,6 +141,8 @@ def main() -> int:
     ap.add_argument("--reuse-plan", action="store_true",
                     help="build the tile plan once, outside the timed steps (a plan serves every layer of a micro-batch)")
     ap.add_argument("--attention-only", action="store_true", help="step = plan + fwd + bwd (no permutes)")
+    ap.add_argument("--no-seed-leg", action="store_true",
+                    help="skip the extra leg that times attention on three more length seeds of the same recipe")
     ap.add_argument("--cost-model", action="store_true",
                     help="only the cost-model leg: time attention fwd+bwd on 24 synthetic batches, fit the "
                          "paper's alpha-beta computation model (Eq. 12) on half of them, report the error on all")
@@ -229,15 +231,26 @@ def main() -> int:
     torch.cuda.synchronize()
 
     ctx.profile_start(16 * max(args.steps, 1))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # per-step min / median only
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(stream)
+    for i in range(args.steps):
         step()
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = ctx.profile_stop()
 
     ms_step = (t1 - t0) * 1e3 / max(args.steps, 1)
+    per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+
+    # plan creation by itself (host time per create + destroy; the upload is asynchronous)
+    torch.cuda.synchronize()
+    tp0 = time.perf_counter()
+    for _ in range(50):
+        fx.Plan(ctx, cu, Hq, Hkv, D, True).close()
+    plan_ms = (time.perf_counter() - tp0) * 1e3 / 50
     tflops = (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12
 
     kern = {}
@@ -257,7 +270,9 @@ def main() -> int:
     out = {
         "metric": "varlen causal attn fwd+bwd TFLOP/s (1 GPU) and % of bf16 MFMA peak",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_step, "ms_per_step_min": min(per_step) if per_step else None,
+        "ms_per_step_median": float(np.median(per_step)) if per_step else None,
+        "plan_create_destroy_host_ms": plan_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "tokens": T, "sequences": len(lens), "max_len": max(lens),
                    "hq": Hq, "hkv": Hkv, "head_dim": D, "causal": True, "sp_degree": P,
@@ -272,6 +287,33 @@ def main() -> int:
 
     if not args.no_permute_leg:
         out["permute"] = permute_leg(ctx, fx, wl, torch, stream)
+
+    # ---- the same recipe with other length seeds (the pareto recipe is seed-sensitive): plan + fwd + bwd
+    if not args.no_seed_leg and cfg.name == "pareto-64k":
+        legs = []
+        for k_ in (1, 2, 3):
+            lens_k = wl.lengths(cfg, seed=cfg.seed + k_)
+            cu_k = wl.cu_seqlens(lens_k)
+            cud_k = torch.from_numpy(cu_k).to(dev)
+            fl = sum(wl.attn_flops(lens_k, Hq, D, True))
+
+            def attn_step():
+                plan = fx.Plan(ctx, cu_k, Hq, Hkv, D, True)
+                fx.flexsp_attn_varlen_fwd(ctx, plan, v3(sq), v3(sk), v3(sv), cud_k, v3(so), lse, stream=stream)
+                fx.flexsp_attn_varlen_bwd(ctx, plan, v3(sq), v3(sk), v3(sv), v3(so), v3(sg), lse, cud_k,
+                                          v3(sdq), v3(sdk), v3(sdv), stream=stream)
+                plan.close()
+            for _ in range(3):
+                attn_step()
+            torch.cuda.synchronize()
+            ts0 = time.perf_counter()
+            for _ in range(10):
+                attn_step()
+            torch.cuda.synchronize()
+            ms_k = (time.perf_counter() - ts0) * 1e3 / 10
+            legs.append({"length_seed": cfg.seed + k_, "sequences": len(lens_k), "max_len": max(lens_k),
+                         "flops_fwd_bwd": fl, "ms_per_step": ms_k, "tflops": fl / (ms_k * 1e-3) / 1e12})
+        out["other_length_seeds_attention_only"] = legs
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     if not args.no_cpu_baseline:

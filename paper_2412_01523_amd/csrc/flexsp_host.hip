@@ -177,6 +177,12 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
 {
     std::vector<Work> work;
     std::vector<int64_t> group_cost;
+    {
+        size_t total = 0;
+        for (int b = 0; b < B; b++) total += (size_t)cdiv(std::max(cu[b + 1] - cu[b], 0), tile_rows);
+        work.reserve(total * heads);
+        group_cost.reserve((size_t)B * heads);
+    }
     for (int b = 0; b < B; b++) {
         int32_t s = cu[b + 1] - cu[b];
         if (s <= 0) continue;
@@ -222,53 +228,72 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
         queue_of[g] = best;
         load[best] += group_cost[g];
     }
-    // item -> queue: its group's queue, then level the queues by moving the cheapest items of the
-    // fullest queue to the emptiest one (a group that outweighs a whole queue's share, e.g. one
-    // dominant sequence with few heads, is split this way; only the moved items lose L2 affinity)
-    std::vector<int32_t> item_queue(work.size());
-    for (size_t i = 0; i < work.size(); i++) item_queue[i] = queue_of[work[i].group];
+    // item -> queue: its group's queue.  Each queue's members are kept in order of decreasing
+    // cost; the order comes from one stable counting sort of all items (costs are small integers),
+    // not from comparison sorts: a plan is built per micro-batch, on the host's time.
+    const size_t n = work.size();
+    std::vector<int32_t> item_queue(n);
+    for (size_t i = 0; i < n; i++) item_queue[i] = queue_of[work[i].group];
+    std::vector<int32_t> by_cost(n);  // item indices, most expensive first, ties in list order
     {
-        std::vector<std::vector<int32_t>> members(nq);
-        for (size_t i = 0; i < work.size(); i++) members[item_queue[i]].push_back((int32_t)i);
-        for (int x = 0; x < nq; x++)  // cheapest last
-            std::stable_sort(members[x].begin(), members[x].end(),
+        int64_t maxc = 0;
+        for (const Work &w : work) maxc = std::max(maxc, w.cost);
+        if (maxc <= (int64_t)(4 * n + 1024)) {
+            std::vector<int32_t> start((size_t)maxc + 2, 0);
+            for (const Work &w : work) start[(size_t)(maxc - w.cost) + 1]++;
+            for (size_t c = 1; c < start.size(); c++) start[c] += start[c - 1];
+            for (size_t i = 0; i < n; i++) by_cost[(size_t)start[(size_t)(maxc - work[i].cost)]++] = (int32_t)i;
+        } else {  // a few enormous items: the table would be larger than the list
+            for (size_t i = 0; i < n; i++) by_cost[i] = (int32_t)i;
+            std::stable_sort(by_cost.begin(), by_cost.end(),
                              [&](int32_t a, int32_t b) { return work[a].cost > work[b].cost; });
-        for (size_t guard = 0; guard < work.size(); guard++) {
-            int hi = 0, lo_ = 0;
-            for (int x = 1; x < nq; x++) {
-                if (load[x] > load[hi]) hi = x;
-                if (load[x] < load[lo_]) lo_ = x;
-            }
-            if (members[hi].empty()) break;
-            const int32_t cand = members[hi].back();
-            const int64_t c = work[cand].cost;
-            if (load[hi] - c < load[lo_] + c) break;  // moving would not narrow the gap
-            members[hi].pop_back();
-            load[hi] -= c;
-            load[lo_] += c;
-            item_queue[cand] = lo_;
-            // keep the receiving queue ordered (cheapest last)
-            auto pos = std::upper_bound(members[lo_].begin(), members[lo_].end(), cand,
-                                        [&](int32_t a, int32_t b) { return work[a].cost > work[b].cost; });
-            members[lo_].insert(pos, cand);
         }
     }
-    std::vector<int32_t> perm(work.size());
-    for (size_t i = 0; i < perm.size(); i++) perm[i] = (int32_t)i;
-    std::stable_sort(perm.begin(), perm.end(), [&](int32_t a, int32_t b) {
-        if (item_queue[a] != item_queue[b]) return item_queue[a] < item_queue[b];
-        return work[a].cost > work[b].cost;
-    });
-    out.items.resize(work.size());
-    for (int x = 0; x <= kMaxQueues; x++) out.offsets[x] = (int64_t)work.size();
-    out.offsets[0] = 0;
-    int cur = 0;
-    for (size_t i = 0; i < perm.size(); i++) {
-        out.items[i] = work[perm[i]].it;
-        int qx = item_queue[perm[i]];
-        while (cur < qx) out.offsets[++cur] = (int64_t)i;
+    std::vector<std::vector<int32_t>> members(nq);
+    for (int x = 0; x < nq; x++) members[x].reserve(n / nq + 16);
+    for (int32_t idx : by_cost) members[item_queue[idx]].push_back(idx);
+    // Level the queues by moving the cheapest items of the fullest queue to the emptiest one (a
+    // group that outweighs a whole queue's share, e.g. one dominant sequence with few heads, is
+    // split this way; only the moved items lose L2 affinity).
+    // Moved items wait in a side list per receiving queue and are merged in once (one insertion
+    // into a sorted list per move costs a memmove each, thousands of times when six heavy groups
+    // meet eight queues).
+    auto dearer = [&](int32_t a, int32_t b) { return work[a].cost > work[b].cost; };
+    std::vector<std::vector<int32_t>> incoming(nq);
+    auto merge_in = [&](int x) {
+        if (incoming[x].empty()) return;
+        std::stable_sort(incoming[x].begin(), incoming[x].end(), dearer);
+        std::vector<int32_t> merged(members[x].size() + incoming[x].size());
+        std::merge(members[x].begin(), members[x].end(), incoming[x].begin(), incoming[x].end(), merged.begin(),
+                   dearer);
+        members[x].swap(merged);
+        incoming[x].clear();
+    };
+    for (size_t guard = 0; guard < n; guard++) {
+        int hi = 0, lo_ = 0;
+        for (int x = 1; x < nq; x++) {
+            if (load[x] > load[hi]) hi = x;
+            if (load[x] < load[lo_]) lo_ = x;
+        }
+        merge_in(hi);  // (rare: a queue that received items has become the fullest)
+        if (members[hi].empty()) break;
+        const int32_t cand = members[hi].back();
+        const int64_t c = work[cand].cost;
+        if (load[hi] - c < load[lo_] + c) break;  // moving would not narrow the gap
+        members[hi].pop_back();
+        load[hi] -= c;
+        load[lo_] += c;
+        incoming[lo_].push_back(cand);
     }
-    while (cur < nq) out.offsets[++cur] = (int64_t)work.size();
+    for (int x = 0; x < nq; x++) merge_in(x);
+    out.items.resize(n);
+    size_t at = 0;
+    for (int x = 0; x <= kMaxQueues; x++) out.offsets[x] = (int64_t)n;
+    for (int x = 0; x < nq; x++) {
+        out.offsets[x] = (int64_t)at;
+        for (int32_t idx : members[x]) out.items[at++] = work[idx].it;
+    }
+    out.offsets[nq] = (int64_t)n;
     out.tile_rows = tile_rows;
 }
 

@@ -136,6 +136,8 @@ SMALL_CASES = [
     ("noncausal", [17, 64, 100, 255, 130], 2, 2, 128, False),
     ("noncausal-gqa-d64", [70, 129, 1], 4, 2, 64, False),
     ("several-tiles", [1500, 700], 2, 2, 128, True),
+    ("several-tiles-gqa-d64", [900, 333], 2, 1, 64, True),
+    ("noncausal-several-tiles", [700, 200], 2, 2, 128, False),
 ]
 
 

@@ -131,6 +131,23 @@ def test_plan_levels_queues_when_one_sequence_dominates(host_ctx):
     plan.close()
 
 
+def test_plan_with_few_enormous_items_takes_the_comparison_sort_path(host_ctx):
+    """One 200 000-token sequence, non-causal, one kv head for sixteen query heads: the dK/dV pass
+    has 3 125 items of 50 000 steps each, so a table indexed by cost would be larger than the list
+    and the builder sorts by comparison instead; the same invariants hold."""
+    lens = [200000, 70, 0, 3]
+    plan = fx.Plan(host_ctx, wl.cu_seqlens(lens), 16, 1, 128, False)
+    for which, heads in ((fx.PASS_FWD, 16), (fx.PASS_BWD_DKV, 1), (fx.PASS_BWD_DQ, 16)):
+        rows = plan.tile_rows(which)
+        items, offs = _check_pass(plan, which, lens, heads, rows)
+        for x in range(len(offs) - 1):   # cost = the sequence's length here (every tile sees every row)
+            seg = [int(i["seq_len"]) for i in items[offs[x]:offs[x + 1]]]
+            assert all(a >= b for a, b in zip(seg, seg[1:]))
+        sizes = np.diff(offs)
+        assert sizes.max() - sizes.min() <= 2 + len(lens) * heads   # equal-cost items: queues level out
+    plan.close()
+
+
 def test_permute_and_attention_validation_without_a_device(host_ctx):
     L = fx.lib()
     h = host_ctx.handle

@@ -230,9 +230,10 @@ def test_peaky_softmax_moves_the_running_maximum_often(ctx):
             assert_close("O", bf16_f64(out["O"]), O)
             assert np.abs(out["LSE"] - LSE).max() < 1e-3 * max(1.0, float(np.abs(LSE).max()) / 16), "LSE"
             for name in ("dQ", "dK", "dV"):
-                # the absolute bound is stated for unit-variance inputs: with q six times larger it is
-                # scaled by six (dK is linear in q); the relative L2 bound stays as stated
-                tol = 6 * MAX_ABS if grad_f32 else np.maximum(6 * MAX_ABS, err32[name] + 2.0 ** -8 * np.abs(ref[name]))
+                # the absolute bound is stated for unit-variance inputs, whose gradients stay within about
+                # +-2; here they reach 20, so it is scaled by max|ref| / 2; the relative L2 bound stays
+                base = MAX_ABS * max(1.0, float(np.abs(ref[name]).max()) / 2)
+                tol = base if grad_f32 else np.maximum(base, err32[name] + 2.0 ** -8 * np.abs(ref[name]))
                 ma, rl = assert_close(f"peaky {name} causal={causal} grad_f32={grad_f32}", out[name], ref[name], max_abs=tol)
                 if grad_f32:
                     err32[name] = ma

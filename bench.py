@@ -177,6 +177,8 @@ def main() -> int:
     cu = wl.cu_seqlens(lens)
     T, Hq, Hkv, D = cfg.tokens, cfg.hq, cfg.hkv, cfg.d
     P = cfg.sp_degree if cfg.sp_degree else 8
+    while T % P:      # the permutes split the token stream into P equal chunks
+        P //= 2
     Tl = T // P
     f_fwd, f_bwd = wl.attn_flops(lens, Hq, D, True)
     pairs_heads = wl.causal_pairs(lens) * Hq

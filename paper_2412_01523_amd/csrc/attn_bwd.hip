@@ -134,7 +134,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             lo.pin();
             wait_vmem();
             __syncthreads();  // tile `step` is in LDS; the previous step's exchange slots are free
-            if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
+            // (the copies of the next tiles go out after phase 1's matrix instructions, not here: a
+            // wavefront waits until its copy instructions are accepted, and behind the barrier that wait
+            // would sit in front of matrix work that is ready to go; about 1 % on batches of short
+            // sequences; the same move in the dQ kernel cost 2 %)
 
             // ---- phase 1: P and dS of query block j
             uint32_t pp[8], dd[8];
@@ -159,6 +162,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                             sacc = mfma32(fr[n], kf[n >> 1], sacc);
                     }
                 }
+                if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
                 // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e
                 const bool masked = (a.causal && my_lo < wk_lo + 31) || (my_lo + 32 > s);
                 auto probs = [&](auto maskc) {
@@ -192,6 +196,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 *(u32x4 *)(slot) = j ? u32x4{pp[0], pp[1], pp[2], pp[3]} : u32x4{dd[0], dd[1], dd[2], dd[3]};
                 *(u32x4 *)(slot + 1024) = j ? u32x4{pp[4], pp[5], pp[6], pp[7]} : u32x4{dd[4], dd[5], dd[6], dd[7]};
             }
+            if (empty(j) && step + 1 < total) prefetch(step + 1, BUF ^ 1);  // no phase 1: the copies go out here
             __syncthreads();  // the partner's fragments are visible
 
             // ---- phase 2: role 0: dV^T += dO^T P, role 1: dK^T += Q^T dS, both query blocks

@@ -75,49 +75,8 @@ def cost_model_leg(ctx, fx, wl, torch, np):
     reports the relative error on every batch (the paper reports < 6 %)."""
     from paper_2412_01523_amd import cost_model as cm
     H, D = 8, 128
-    rng = np.random.Generator(np.random.Philox(key=[wl.BASE_SEED, 4242]))
-
-    def fill(draw, total):
-        out, left = [], total
-        while left > 0:
-            s = min(int(draw()), left)
-            out.append(s)
-            left -= s
-        return out
-
-    batches = []
-    for total in (16384, 32768, 65536, 131072):
-        batches.append(fill(lambda: np.clip(np.rint(np.exp(rng.normal(7.0, 1.2))), 128, 32768), total))
-        batches.append(fill(lambda: np.clip(np.floor(256.0 * (1.0 - rng.random()) ** (-1 / 1.1)), 256, 65536), total))
-        batches.append(fill(lambda: rng.integers(64, 1025), total))
-        batches.append(fill(lambda: rng.integers(2048, 8193), total))
-        batches.append([total // 4] * 4)
-        batches.append([total])
-    times = []
-    for lens in batches:
-        cu = wl.cu_seqlens(lens)
-        T = int(cu[-1])
-        q = torch.randn((T, H, D), device="cuda", dtype=torch.float32).to(torch.bfloat16)
-        k, v, g = torch.randn_like(q), torch.randn_like(q), torch.randn_like(q)
-        o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
-        lse = torch.empty((H, T), dtype=torch.float32, device="cuda")
-        cud = torch.from_numpy(cu).cuda()
-        plan = fx.Plan(ctx, cu, H, H, D, True)
-
-        def once():
-            fx.flexsp_attn_varlen_fwd(ctx, plan, q, k, v, cud, o, lse)
-            fx.flexsp_attn_varlen_bwd(ctx, plan, q, k, v, o, g, lse, cud, dq, dk, dv)
-
-        once(); once()
-        reps = []
-        for _ in range(5):
-            ctx.profile_start(8)
-            once()
-            pr = ctx.profile_stop()
-            reps.append(sum(pr[kk][0] for kk in ("fwd", "bwd_delta", "bwd_dkv", "bwd_dq")))
-        times.append(float(np.median(reps)))
-        plan.close()
-        del q, k, v, g, o, dq, dk, dv, lse
+    batches = cm.synthetic_batches(seed=wl.BASE_SEED)
+    times = cm.profile(ctx, batches, H, D)
     coef = cm.fit(batches[0::2], times[0::2])
     err = cm.relative_errors(coef, batches, times)
     return {"alpha1_ms_per_token2": coef[0], "alpha2_ms_per_token": coef[1], "beta1_ms": coef[2],

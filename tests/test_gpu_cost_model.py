@@ -1,0 +1,34 @@
+"""The paper's computation-cost model (Sec. 4.1.2, Eq. 12: T = alpha1 sum s^2 + alpha2 sum s + beta1,
+coefficients "obtained through profiling", estimation error reported below 6 %) fitted to this
+library's attention kernels on the GPU: profile seeded synthetic batches of 32K to 128K tokens,
+fit on every second one, and require the model to predict the held-out ones."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2412_01523_amd import cost_model as cm
+from paper_2412_01523_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def test_eq12_fit_predicts_held_out_batches():
+    from paper_2412_01523_amd import binding as fx
+    ctx = fx.Context(0)
+    batches = cm.synthetic_batches(totals=(32768, 65536, 131072), seed=wl.BASE_SEED)
+    times = cm.profile(ctx, batches, heads=8, head_dim=128, reps=5)
+    ctx.close()
+    fit_b, fit_t = batches[0::2], times[0::2]
+    held_b, held_t = batches[1::2], times[1::2]
+    coef = cm.fit(fit_b, fit_t)
+    e_fit = cm.relative_errors(coef, fit_b, fit_t)
+    e_held = cm.relative_errors(coef, held_b, held_t)
+    for b, t, e in zip(batches, times, cm.relative_errors(coef, batches, times)):
+        print(f"  tokens {sum(b):6d} sequences {len(b):3d} longest {max(b):6d}: {t:8.3f} ms, model {100 * e:+.1f} %", flush=True)
+    print(f"alpha1={coef[0]:.4e} ms/token^2 alpha2={coef[1]:.4e} ms/token beta1={coef[2]:.4e} ms; "
+          f"max |error| fitted {100 * np.abs(e_fit).max():.1f} %, held out {100 * np.abs(e_held).max():.1f} %", flush=True)
+    sys.stdout.flush()
+    assert coef[0] > 0                                  # the quadratic term is the attention itself
+    assert np.abs(e_held).max() <= 0.08
+    assert np.abs(e_fit).max() <= 0.08

@@ -9,7 +9,8 @@ import pytest
 import oracle
 from paper_2412_01523_amd import workloads as wl
 
-from gpu_util import MAX_ABS, GpuAttn, assert_close, bf16_f64, bf16_store_tol, to_bits, to_dev
+from gpu_util import (MAX_ABS, GpuAttn, assert_close, bf16_f64, check_against_budget, round_to_bf16, to_bits,
+                      to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -141,54 +142,43 @@ SMALL_CASES = [
 ]
 
 
+def _check_case(ctx, tag, lens, Hq, Hkv, D, causal, seed, qmul=1.0, scale=0.0):
+    """One packed batch through the HIP path in both gradient modes, every element against the
+    oracle: inside the budget the kernels' roundings allow, inside relative L2 5e-3, inside the
+    stated max-abs 2e-2 (see check_against_budget; `qmul` != 1 marks inputs outside the N(0,1)
+    recipe the flat bound is stated for), and the bf16-gradient run must equal the fp32-gradient
+    run rounded to bf16 bit for bit (the two modes differ in the final store only)."""
+    T = sum(lens)
+    cu = wl.cu_seqlens(lens)
+    q = wl.normal_bf16(seed, wl.TID_Q, (T, Hq, D))
+    if qmul != 1.0:
+        q = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(q) * np.float32(qmul))
+    k = wl.normal_bf16(seed, wl.TID_K, (T, Hkv, D))
+    v = wl.normal_bf16(seed, wl.TID_V, (T, Hkv, D))
+    g = wl.normal_bf16(seed, wl.TID_DO, (T, Hq, D))
+    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, causal, scale if scale else None)
+    ref = {"O": O, "dQ": dQ, "dK": dK, "dV": dV}
+    lse_tol = 1e-3 * max(1.0, float(np.abs(LSE).max()) / 16) if T else 1e-3   # fp32 spacing grows with |LSE|
+    runs = {}
+    for grad_f32 in (True, False):
+        out = GpuAttn(ctx).run(q, k, v, g, cu, causal, scale=scale, grad_f32=grad_f32)
+        assert np.abs(out["LSE"] - LSE).max(initial=0.0) < lse_tol, "LSE"
+        res = check_against_budget(f"{tag} grad_f32={grad_f32}", out, ref, q, k, v, g, cu, causal, scale,
+                                   grad_f32, stated=(qmul == 1.0))
+        say(f"  grad_f32={grad_f32} (max_abs, rel_l2, share of the rounding budget): " +
+            " ".join(f"{k_}=({a:.2e},{b:.2e},{c:.2f})" for k_, (a, b, c) in res.items()))
+        runs[grad_f32] = out
+    for name in ("dQ", "dK", "dV"):
+        assert np.array_equal(runs[False][name], round_to_bf16(runs[True][name])), \
+            f"{tag} {name}: bf16 gradients are not the fp32 gradients rounded once"
+    assert np.array_equal(runs[False]["O"], runs[True]["O"])
+    return ref
+
+
 @pytest.mark.parametrize("name,lens,Hq,Hkv,D,causal", SMALL_CASES, ids=[c[0] for c in SMALL_CASES])
 def test_attention_matches_oracle_elementwise(ctx, name, lens, Hq, Hkv, D, causal):
     say(f"attention case {name} lens={lens} Hq={Hq} Hkv={Hkv} D={D} causal={causal}")
-    T = sum(lens)
-    cu = wl.cu_seqlens(lens)
-    seed = 4242 + len(name)
-    q = wl.normal_bf16(seed, wl.TID_Q, (T, Hq, D))
-    k = wl.normal_bf16(seed, wl.TID_K, (T, Hkv, D))
-    v = wl.normal_bf16(seed, wl.TID_V, (T, Hkv, D))
-    g = wl.normal_bf16(seed, wl.TID_DO, (T, Hq, D))
-    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, causal)
-    ref = {"dQ": dQ, "dK": dK, "dV": dV}
-    err32 = {}
-    for grad_f32 in (True, False):
-        out = GpuAttn(ctx).run(q, k, v, g, cu, causal, grad_f32=grad_f32)
-        res = {}
-        res["O"] = assert_close("O", bf16_f64(out["O"]), O)
-        assert np.abs(out["LSE"] - LSE).max() < 1e-3, "LSE"
-        for name in ("dQ", "dK", "dV"):
-            # fp32 gradients: the stated 2e-2.  bf16 gradients: 2e-2, or per element the fp32
-            # result's error plus half a bf16 ulp of the value where that is larger (|value| >= 4).
-            tol = MAX_ABS if grad_f32 else bf16_store_tol(ref[name], err32[name])
-            res[name] = assert_close(name, out[name], ref[name], max_abs=tol)
-            if grad_f32:
-                err32[name] = res[name][0]
-        say(f"  grad_f32={grad_f32} errors (max_abs, rel_l2): " +
-            " ".join(f"{k_}=({a:.2e},{b:.2e})" for k_, (a, b) in res.items()))
-
-
-def _check_case(ctx, tag, lens, Hq, Hkv, D, causal, seed, grad_modes=(True, False)):
-    T = sum(lens)
-    cu = wl.cu_seqlens(lens)
-    q = wl.normal_bf16(seed, wl.TID_Q, (T, Hq, D))
-    k = wl.normal_bf16(seed, wl.TID_K, (T, Hkv, D))
-    v = wl.normal_bf16(seed, wl.TID_V, (T, Hkv, D))
-    g = wl.normal_bf16(seed, wl.TID_DO, (T, Hq, D))
-    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, causal)
-    ref = {"dQ": dQ, "dK": dK, "dV": dV}
-    err32 = {}
-    for grad_f32 in grad_modes:
-        out = GpuAttn(ctx).run(q, k, v, g, cu, causal, grad_f32=grad_f32)
-        assert_close("O", bf16_f64(out["O"]), O)
-        assert np.abs(out["LSE"] - LSE).max() < 1e-3, "LSE"
-        for name in ("dQ", "dK", "dV"):
-            tol = MAX_ABS if grad_f32 else bf16_store_tol(ref[name], err32[name])  # fp32 mode runs first
-            ma, _ = assert_close(f"{tag} {name} grad_f32={grad_f32}", out[name], ref[name], max_abs=tol)
-            if grad_f32:
-                err32[name] = ma
+    _check_case(ctx, name, lens, Hq, Hkv, D, causal, 4242 + len(name))
 
 
 @pytest.mark.parametrize("seed", list(range(12)))
@@ -211,33 +201,14 @@ def test_random_small_configs(ctx, seed):
 def test_peaky_softmax_moves_the_running_maximum_often(ctx):
     """Queries six times larger than N(0,1): scores have a standard deviation of about 6, so the
     running row maximum keeps growing by more than the slack the forward kernel tolerates before it
-    rescales its accumulator, and almost all probability mass sits on a few keys."""
+    rescales its accumulator, and almost all probability mass sits on a few keys.  Gradients reach
+    +-20 here, outside the range the flat 2e-2 is stated for, so the per-element bound is the
+    rounding budget alone (derived from the kernels' roundings before the run; on the CPU an
+    emulation of those roundings uses under 5/8 of it on this kind of input); relative L2 stays 5e-3."""
     lens, Hq, Hkv, D = [700, 129, 64], 2, 2, 128
-    T = sum(lens)
-    cu = wl.cu_seqlens(lens)
-    seed = 8103
-    q = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(wl.normal_bf16(seed, wl.TID_Q, (T, Hq, D))) * np.float32(6.0))
-    k = wl.normal_bf16(seed, wl.TID_K, (T, Hkv, D))
-    v = wl.normal_bf16(seed, wl.TID_V, (T, Hkv, D))
-    g = wl.normal_bf16(seed, wl.TID_DO, (T, Hq, D))
     say(f"peaky softmax: lens={lens}")
     for causal in (True, False):
-        O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, causal)
-        ref = {"dQ": dQ, "dK": dK, "dV": dV}
-        err32 = {}
-        for grad_f32 in (True, False):
-            out = GpuAttn(ctx).run(q, k, v, g, cu, causal, grad_f32=grad_f32)
-            assert_close("O", bf16_f64(out["O"]), O)
-            assert np.abs(out["LSE"] - LSE).max() < 1e-3 * max(1.0, float(np.abs(LSE).max()) / 16), "LSE"
-            for name in ("dQ", "dK", "dV"):
-                # the absolute bound is stated for unit-variance inputs, whose gradients stay within about
-                # +-2; here they reach 20, so it is scaled by max|ref| / 2; the relative L2 bound stays
-                base = MAX_ABS * max(1.0, float(np.abs(ref[name]).max()) / 2)
-                tol = base if grad_f32 else np.maximum(base, err32[name] + 2.0 ** -8 * np.abs(ref[name]))
-                ma, rl = assert_close(f"peaky {name} causal={causal} grad_f32={grad_f32}", out[name], ref[name], max_abs=tol)
-                if grad_f32:
-                    err32[name] = ma
-                say(f"  causal={causal} grad_f32={grad_f32} {name}: max_abs={ma:.2e} rel_l2={rl:.2e} max|ref|={np.abs(ref[name]).max():.1f}")
+        _check_case(ctx, f"peaky causal={causal}", lens, Hq, Hkv, D, causal, 8103, qmul=6.0)
 
 
 def test_many_tiny_sequences_outnumber_the_workgroups(ctx):

@@ -212,6 +212,31 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
                            flexsp_tensor dv, int32_t grad_dtype, flexsp_stream stream);
 
 /*
+ * The forward for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same result as flexsp_attn_varlen_fwd, bit for bit, but it takes
+ * no plan and calls no hipMalloc, hipFree or any other allocating routine: the work queues are built
+ * on the device from `cu_seqlens_dev` (device pointer, B+1 int32 prefix sums, cu[0] = 0,
+ * non-decreasing, cu[B] <= T) by a small kernel launched in front of the attention kernel, into a
+ * fixed array of about 1 MiB that each GPU the library runs on holds from library load until the
+ * process ends (its address on the context's device is resolved by flexsp_ctx_create).
+ *   B, T            sequences in the batch; tokens the q / k / v / o tensors hold (rows of lse)
+ *   D               head dim, 64 or 128; the remaining arguments are those of flexsp_attn_varlen_fwd
+ * Limits: T <= 524 288 and (ceil(T / 128) + B) * head_count <= 65 536, else FLEXSP_UNSUPPORTED.
+ * The lengths are read on the device only, so they cannot be checked by the host: if the device
+ * array is not a valid prefix-sum list inside [0, T], NOTHING is computed (o and lse keep their
+ * contents).  Every call on a GPU shares that GPU's array: calls that may overlap in time on one
+ * GPU (different streams, or graph replays running concurrently) race; order them.  Sequences are
+ * served longest tile first like a plan's queues, but without the plan's grouping of a head's tiles
+ * onto one XCD, so it is somewhat slower than the plan-based call; nothing synchronises the host.
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED, NO_DEVICE, HIP_ERROR.
+ */
+int flexsp_attn_varlen_fwd_static(flexsp_ctx *ctx, flexsp_tensor q, flexsp_tensor k, flexsp_tensor v,
+                                  const int32_t *cu_seqlens_dev, int32_t B, int64_t T, int32_t head_begin,
+                                  int32_t head_count, int32_t kv_head_begin, int32_t kv_head_count, int32_t D,
+                                  int causal, float softmax_scale, flexsp_tensor o, float *lse,
+                                  flexsp_stream stream);
+
+/*
  * ---------------------------------------------------------------------------------------------
  * Planner pieces that are exact and need no external solver (host only, no GPU involved).
  * All lengths are token counts, 0 <= s <= 2^40; arrays are host pointers.

@@ -25,7 +25,7 @@ EXPORTS = (
     "flexsp_plan_create", "flexsp_plan_destroy", "flexsp_plan_num_items", "flexsp_plan_get_items",
     "flexsp_plan_tile_rows", "flexsp_attn_bwd_workspace_bytes",
     "flexsp_pack", "flexsp_unpack", "flexsp_pack_many", "flexsp_unpack_many",
-    "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd",
+    "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd", "flexsp_attn_varlen_fwd_static",
     "flexsp_profile_start", "flexsp_profile_stop",
     "flexsp_bucket_dp", "flexsp_chunk_dp", "flexsp_min_microbatches",
 )
@@ -100,6 +100,9 @@ def lib() -> ctypes.CDLL:
         L.flexsp_attn_varlen_bwd.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, Tensor, Tensor,
                                              c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_int,
                                              c_float, Tensor, Tensor, Tensor, c_int32, c_void_p]
+        L.flexsp_attn_varlen_fwd_static.argtypes = [c_void_p, Tensor, Tensor, Tensor, c_void_p, c_int32, c_int64,
+                                                    c_int32, c_int32, c_int32, c_int32, c_int32, c_int, c_float,
+                                                    Tensor, c_void_p, c_void_p]
         L.flexsp_bucket_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int32), c_void_p,
                                        POINTER(c_int64)]
         L.flexsp_chunk_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int64)]
@@ -282,6 +285,19 @@ def flexsp_attn_varlen_bwd(ctx: Context, plan: Plan, q, k, v, o, dO, lse, cu_seq
                                         head_count, kv_head_begin, kv_head_count, int(bool(causal)),
                                         float(softmax_scale), _view(dq), _view(dk), _view(dv),
                                         grad_dtype, _stream(stream)), "flexsp_attn_varlen_bwd")
+
+
+def flexsp_attn_varlen_fwd_static(ctx: Context, q, k, v, cu_seqlens_dev, o, lse, *, head_begin=0, head_count=None,
+                                  kv_head_begin=0, kv_head_count=None, causal=True, softmax_scale=0.0,
+                                  stream=None):
+    """The forward without a plan and without any allocation (queues built on the device)."""
+    head_count = q.shape[1] - head_begin if head_count is None else head_count
+    kv_head_count = k.shape[1] - kv_head_begin if kv_head_count is None else kv_head_count
+    _check(lib().flexsp_attn_varlen_fwd_static(ctx.handle, _view(q), _view(k), _view(v), cu_seqlens_dev.data_ptr(),
+                                               cu_seqlens_dev.numel() - 1, q.shape[0], head_begin, head_count,
+                                               kv_head_begin, kv_head_count, q.shape[2], int(bool(causal)),
+                                               float(softmax_scale), _view(o), lse.data_ptr(), _stream(stream)),
+           "flexsp_attn_varlen_fwd_static")
 
 
 # ----------------------------------------------------------------------------- planner pieces (host only)

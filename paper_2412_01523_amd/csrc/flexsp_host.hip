@@ -297,17 +297,6 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
     out.tile_rows = tile_rows;
 }
 
-bool view_ok(const flexsp_tensor &t)
-{
-    if (!t.ptr) return false;
-    if (((uintptr_t)t.ptr & 15) != 0) return false;
-    if (t.stride_token <= 0 || t.stride_head <= 0) return false;
-    if ((t.stride_token % 8) != 0 || (t.stride_head % 8) != 0) return false;
-    // kernels use 32-bit strides, and 32-bit per-lane byte offsets that span up to 64 token rows
-    if (t.stride_token > (1 << 24) || t.stride_head > 0x3fffffff) return false;
-    return true;
-}
-
 int check_attn_common(flexsp_ctx *ctx, flexsp_plan *plan, const int32_t *cu_dev, int32_t head_begin,
                       int32_t head_count, int32_t kv_head_begin, int32_t kv_head_count, int causal)
 {
@@ -331,6 +320,11 @@ int grid_for(const flexsp_ctx *ctx, const HostPass &p, int per_cu)
 }
 
 }  // namespace
+
+namespace flexsp {
+int ctx_device(const flexsp_ctx *ctx) { return ctx ? ctx->device : -1; }
+int hip_status(hipError_t e) { return hip_fail(e); }
+}  // namespace flexsp
 
 extern "C" {
 
@@ -385,7 +379,9 @@ int flexsp_ctx_create(flexsp_ctx **out, int device)
         c->num_cu = pr.multiProcessorCount;
         e = hipSetDevice(device);
         if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->upload, hipStreamNonBlocking);
+        if (e == hipSuccess) e = static_scratch_init(device);  // this device is current here
         if (e != hipSuccess) {
+            if (c->upload) (void)hipStreamDestroy(c->upload);
             delete c;
             return hip_fail(e);
         }

@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cmath>
+#include <cstring>
+
 #include "flexsp.h"
 
 namespace flexsp {
@@ -55,5 +58,22 @@ hipError_t launch_pack_many(int n, const void *const *src, void *const *dst, int
 hipError_t launch_attn_fwd(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s);
+
+// Host helpers shared by the files that hold entry points.
+int ctx_device(const flexsp_ctx *ctx);        // HIP device of a context, -1 for a host-only one
+int hip_status(hipError_t e);                 // records e for flexsp_last_hip_error, returns the flexsp_status for it
+hipError_t static_scratch_init(int device);   // resolves the device's copy of the no-allocation scratch array
+
+// A view the attention kernels can address: 16-byte aligned rows, strides that fit the kernels'
+// 32-bit arithmetic (a per-lane byte offset spans up to 64 token rows).
+inline bool view_ok(const flexsp_tensor &t)
+{
+    if (!t.ptr) return false;
+    if (((uintptr_t)t.ptr & 15) != 0) return false;
+    if (t.stride_token <= 0 || t.stride_head <= 0) return false;
+    if ((t.stride_token % 8) != 0 || (t.stride_head % 8) != 0) return false;
+    if (t.stride_token > (1 << 24) || t.stride_head > 0x3fffffff) return false;
+    return true;
+}
 
 }  // namespace flexsp

@@ -36,6 +36,12 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK = 2.5e15     # MI355X dense bf16 MFMA, FLOP/s (256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz)
 HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 
+# HBM bytes per launch of the attention kernels (FETCH_SIZE + WRITE_SIZE from two rocprofv3 --pmc runs,
+# each scaled by what the same counter reads for a plain copy of known size; the commands, the raw
+# counter values and the algorithmic bytes beside them are in profiles/attention_hbm_traffic.md).
+# bench.py cannot run the profiler on itself: these are the figures of that summary.
+MEASURED_HBM_TRAFFIC = {}
+
 
 def permute_leg(ctx, fx, wl, torch, stream):
     """Achieved HBM bandwidth of pack / unpack on the [32768, 32, 128] bf16, P = 8 shape, rotating
@@ -105,6 +111,10 @@ def main() -> int:
     ap.add_argument("--cost-model", action="store_true",
                     help="only the cost-model leg: time attention fwd+bwd on 24 synthetic batches, fit the "
                          "paper's alpha-beta computation model (Eq. 12) on half of them, report the error on all")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for counter collection under rocprofv3 --pmc: 5 plain copies of known size (the permute "
+                         "kernel with P = 1 on [32768, 32, 128] bf16: 256 MiB read, 256 MiB written each), then 3 x "
+                         "(forward + backward) of the workload with one plan; nothing is timed")
     ap.add_argument("--permute-only", action="store_true",
                     help="only the permute bandwidth leg: 50 pack, 50 unpack, 50 plain copies (pack with P = 1), "
                          "in that order (for counter collection)")
@@ -123,6 +133,41 @@ def main() -> int:
         torch.cuda.set_device(0)
         ctx = fx.Context(0)
         print(json.dumps({"cost_model": cost_model_leg(ctx, fx, wl, torch, np)}))
+        return 0
+
+    if args.traffic_probe:
+        torch.cuda.set_device(0)
+        ctx = fx.Context(0)
+        cfg = next(c for c in wl.CONFIGS if c.name == args.workload)
+        lens = wl.lengths(cfg)
+        cu = wl.cu_seqlens(lens)
+        c1 = wl.CONFIGS[1]
+        src = torch.randn((c1.tokens, c1.hq * c1.sp_degree, c1.d), device="cuda").to(torch.bfloat16)
+        dst = torch.empty((1,) + tuple(src.shape), dtype=torch.bfloat16, device="cuda")
+        for _ in range(5):
+            fx.flexsp_pack(ctx, src, dst, 1)
+        torch.cuda.synchronize()
+        del src, dst
+        T, Hq, Hkv, D = cfg.tokens, cfg.hq, cfg.hkv, cfg.d
+        q = torch.randn((T, Hq, D), device="cuda").to(torch.bfloat16)
+        k = torch.randn((T, Hkv, D), device="cuda").to(torch.bfloat16)
+        v, g = torch.randn_like(k), torch.randn_like(q)
+        o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(k), torch.empty_like(k)
+        lse = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+        cud = torch.from_numpy(cu).cuda()
+        plan = fx.Plan(ctx, cu, Hq, Hkv, D, True)
+        for _ in range(3):
+            fx.flexsp_attn_varlen_fwd(ctx, plan, q, k, v, cud, o, lse)
+            fx.flexsp_attn_varlen_bwd(ctx, plan, q, k, v, o, g, lse, cud, dq, dk, dv)
+        torch.cuda.synchronize()
+        plan.close()
+        # algorithmic bytes per launch: every input read once, every output written once
+        e = 2
+        alg = {"fwd": (T * (2 * Hq + 2 * Hkv) * D) * e + 4 * Hq * T,
+               "bwd_dq": (T * (4 * Hq + 2 * Hkv) * D) * e + 3 * 4 * Hq * T,
+               "bwd_dkv": (T * (2 * Hq + 4 * Hkv) * D) * e + 2 * 4 * Hq * T}
+        print(json.dumps({"traffic_probe": cfg.name, "copy_bytes_each_way": c1.tokens * c1.hq * c1.sp_degree * c1.d * 2,
+                          "algorithmic_bytes_per_launch": alg}))
         return 0
 
     if args.permute_only:
@@ -191,8 +236,10 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    ctx.profile_start(16 * max(args.steps, 1))
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # per-step min / median only
+    # ---- the timed region: K steps, nothing but the path itself between the two synchronisations
+    # (the library's per-kernel event recorder is OFF here; one stream marker per step gives the
+    # per-step minimum and median)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     marks[0].record(stream)
@@ -201,10 +248,17 @@ def main() -> int:
         marks[i + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = ctx.profile_stop()
-
     ms_step = (t1 - t0) * 1e3 / max(args.steps, 1)
     per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+
+    # ---- a second pass over the same steps with the per-kernel recorder on (HIP events around every
+    # launch, on the stream the kernels run on): the per-kernel split and the roofline object.  Not part
+    # of `value` / `ms_per_step`.
+    ctx.profile_start(16 * max(args.steps, 1))
+    for i in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = ctx.profile_stop()
 
     # plan creation by itself (host time per create + destroy; the upload is asynchronous)
     torch.cuda.synchronize()
@@ -225,14 +279,15 @@ def main() -> int:
     dom = max((k for k in alg if k in kern), key=lambda k: kern[k]["avg_ms"] * kern[k]["launches_per_step"])
     ach = alg[dom] / (kern[dom]["avg_ms"] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK / 1e12,
-                "unit": "TFLOP/s", "frac": ach / (BF16_MFMA_PEAK / 1e12), "traffic": None,
-                "avg_ms": kern[dom]["avg_ms"]}
+                "unit": "TFLOP/s", "frac": ach / (BF16_MFMA_PEAK / 1e12),
+                "traffic": MEASURED_HBM_TRAFFIC.get((cfg.name, dom)), "avg_ms": kern[dom]["avg_ms"]}
     attn_ms = sum(kern[k]["avg_ms"] * kern[k]["launches_per_step"] for k in ("fwd", "bwd_delta", "bwd_dkv", "bwd_dq") if k in kern)
     out = {
         "metric": "varlen causal attn fwd+bwd TFLOP/s (1 GPU) and % of bf16 MFMA peak",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "ms_per_step_min": min(per_step) if per_step else None,
         "ms_per_step_median": float(np.median(per_step)) if per_step else None,
+        "ms_per_step_max": max(per_step) if per_step else None,
         "plan_create_destroy_host_ms": plan_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "tokens": T, "sequences": len(lens), "max_len": max(lens),
@@ -246,6 +301,8 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    if os.environ.get("BENCH_DUMP_STEPS"):
+        out["per_step"] = per_step
     if not args.no_permute_leg:
         out["permute"] = permute_leg(ctx, fx, wl, torch, stream)
 
@@ -264,16 +321,24 @@ def main() -> int:
                 fx.flexsp_attn_varlen_bwd(ctx, plan, v3(sq), v3(sk), v3(sv), v3(so), v3(sg), lse, cud_k,
                                           v3(sdq), v3(sdk), v3(sdv), stream=stream)
                 plan.close()
-            for _ in range(3):
-                attn_step()
-            torch.cuda.synchronize()
-            ts0 = time.perf_counter()
             for _ in range(10):
                 attn_step()
             torch.cuda.synchronize()
-            ms_k = (time.perf_counter() - ts0) * 1e3 / 10
+            n_k = 20
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_k + 1)]
+            ts0 = time.perf_counter()
+            ev[0].record(stream)
+            for i in range(n_k):
+                attn_step()
+                ev[i + 1].record(stream)
+            torch.cuda.synchronize()
+            ms_k = (time.perf_counter() - ts0) * 1e3 / n_k
+            each = [ev[i].elapsed_time(ev[i + 1]) for i in range(n_k)]
+            med = float(np.median(each))
             legs.append({"length_seed": cfg.seed + k_, "sequences": len(lens_k), "max_len": max(lens_k),
-                         "flops_fwd_bwd": fl, "ms_per_step": ms_k, "tflops": fl / (ms_k * 1e-3) / 1e12})
+                         "flops_fwd_bwd": fl, "steps": n_k, "ms_per_step": ms_k, "ms_per_step_min": min(each),
+                         "ms_per_step_median": med, "ms_per_step_max": max(each),
+                         "tflops": fl / (ms_k * 1e-3) / 1e12, "tflops_median_step": fl / (med * 1e-3) / 1e12})
         out["other_length_seeds_attention_only"] = legs
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload

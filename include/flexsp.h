@@ -20,9 +20,13 @@
  *     caller; "host pointer" = ordinary host memory, copied before the call returns.
  *   - The four hot calls (pack, unpack, fwd, bwd) are asynchronous on the caller's HIP
  *     stream, allocate nothing and never synchronise the host.
- *   - The library owns only contexts and plans.  A plan may be used by one in-flight
- *     forward and one in-flight backward at a time (each has its own queue counters);
- *     launches that share a plan must be ordered on one stream or by events.
+ *   - The library owns only contexts and plans.  A plan is passed to the hot calls as a
+ *     NON-const pointer on purpose: it owns device memory the kernels WRITE while they run
+ *     (the ticket counters of its work queues, which the last workgroup of a launch clears
+ *     again, and the backward's fp32 scratch), and the host side notes which stream used it
+ *     last.  So a plan may be used by one in-flight forward and one in-flight backward at a
+ *     time (each has its own queue counters); launches that share a plan must be ordered on
+ *     one stream or by events, and two host threads must not launch through one plan at once.
  *   - There is no CPU fallback: without a usable gfx950 device the hot calls fail.
  */
 #ifndef FLEXSP_H
@@ -179,7 +183,11 @@ typedef struct flexsp_tensor {
  *   LSE[h,i] = natural-log-sum-exp of the scaled scores of row i.
  *   q, o              views of [T, *, D] bf16; heads head_begin .. head_begin+head_count-1 are used
  *   k, v              views of [T, *, D] bf16; kv heads kv_head_begin .. +kv_head_count-1
- *   cu_seqlens_dev    device pointer, B+1 int32, same values the plan was built from
+ *   cu_seqlens_dev    the device copy of the prefix sums (B+1 int32), or NULL.  The plan already
+ *                     holds every length (its work items carry each sequence's start and size),
+ *                     so the plan-based calls neither read nor check this array; it is part of
+ *                     the signature because the path's callers have it at hand, and
+ *                     flexsp_attn_varlen_fwd_static, which has no plan, works from it alone
  *   head_count, kv_head_count must equal the plan's Hq, Hkv
  *   softmax_scale     <= 0 selects 1/sqrt(D)
  *   lse               device pointer, fp32 [head_count, T]

@@ -27,7 +27,8 @@ struct PlanSlab {
     hipEvent_t done = nullptr;   // recorded on the last stream that ran kernels on this slab
     bool done_valid = false;
 };
-constexpr size_t kSlabPoolMax = 8;
+constexpr size_t kSlabPoolMax = 8;  // free slabs kept by a context
+constexpr size_t kSlabEager = 3;    // slabs a context makes rather than wait for a busy one
 
 struct flexsp_ctx {
     int device;  // -1: host-only
@@ -35,6 +36,7 @@ struct flexsp_ctx {
     int num_xcd;
     hipStream_t upload = nullptr;  // non-blocking stream (default priority) for plan uploads
     std::vector<PlanSlab> slabs;   // free slabs
+    size_t slabs_owned = 0;        // slabs alive: free ones and those held by plans
     // profiling: a pool of event pairs created by flexsp_profile_start
     bool profiling;
     std::vector<EventPair> events;
@@ -87,17 +89,31 @@ void slab_free(PlanSlab &s)
     s = PlanSlab();
 }
 
-// A slab with at least the given sizes: the smallest adequate one from the pool, else a new one
-// (a quarter larger than asked, so that the next, slightly different batch fits too).
+// A slab with at least the given sizes.  Among the adequate ones in the pool, one whose last
+// kernels have already finished is preferred (the smallest such): its queues can be uploaded at
+// once, while the kernels of the plan destroyed a moment ago still run.  Taking back the slab just
+// released instead would put every step's upload behind the previous step's last kernel and in
+// front of its own first one, an idle gap per step.  When every adequate slab is still in use
+// and the context owns fewer than kSlabEager, a new one is made (a quarter larger than asked, so
+// that the next, slightly different batch fits too); allocating device and pinned memory takes
+// milliseconds and disturbs running kernels, so it is confined to the first steps of a run: a plan
+// per micro-batch settles on kSlabEager slabs taken in turn.  Beyond that a busy slab is taken,
+// the one released longest ago, ordered after its kernels by its event.
 hipError_t slab_get(flexsp_ctx *ctx, size_t dev_bytes, size_t host_bytes, PlanSlab &out)
 {
-    int best = -1;
+    int best = -1, best_busy = -1;
     for (size_t i = 0; i < ctx->slabs.size(); i++) {
         const PlanSlab &s = ctx->slabs[i];
-        if (s.dev_bytes >= dev_bytes && s.host_bytes >= host_bytes &&
-            (best < 0 || s.dev_bytes < ctx->slabs[best].dev_bytes))
-            best = (int)i;
+        if (s.dev_bytes < dev_bytes || s.host_bytes < host_bytes) continue;
+        const bool idle = !s.done_valid || hipEventQuery(s.done) == hipSuccess;
+        // idle: the smallest adequate one; busy: the first in the list, which was released first
+        if (idle) {
+            if (best < 0 || s.dev_bytes < ctx->slabs[best].dev_bytes) best = (int)i;
+        } else if (best_busy < 0) {
+            best_busy = (int)i;
+        }
     }
+    if (best < 0 && best_busy >= 0 && ctx->slabs_owned >= kSlabEager) best = best_busy;
     if (best >= 0) {
         out = ctx->slabs[best];
         ctx->slabs.erase(ctx->slabs.begin() + best);
@@ -115,6 +131,7 @@ hipError_t slab_get(flexsp_ctx *ctx, size_t dev_bytes, size_t host_bytes, PlanSl
         slab_free(s);
         return e;
     }
+    ctx->slabs_owned++;
     out = s;
     return hipSuccess;
 }
@@ -300,7 +317,8 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
 int check_attn_common(flexsp_ctx *ctx, flexsp_plan *plan, const int32_t *cu_dev, int32_t head_begin,
                       int32_t head_count, int32_t kv_head_begin, int32_t kv_head_count, int causal)
 {
-    if (!ctx || !plan || !cu_dev) return FLEXSP_INVALID_ARGUMENT;
+    (void)cu_dev;  // the plan carries the lengths; the device copy is not read by the plan-based calls
+    if (!ctx || !plan) return FLEXSP_INVALID_ARGUMENT;
     if (plan->ctx != ctx) return FLEXSP_PLAN_MISMATCH;
     if (head_begin < 0 || kv_head_begin < 0 || head_count <= 0 || kv_head_count <= 0)
         return FLEXSP_INVALID_ARGUMENT;
@@ -541,6 +559,7 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
         if (e != hipSuccess) {
             (void)hipStreamSynchronize(ctx->upload);
             slab_free(p->slab);
+            ctx->slabs_owned--;
             delete p;
             return hip_fail(e);
         }
@@ -573,11 +592,13 @@ void flexsp_plan_destroy(flexsp_plan *plan)
                 if (s.done_valid) (void)hipEventSynchronize(s.done);
                 (void)hipEventSynchronize(s.ready);
                 slab_free(s);
+                ctx->slabs_owned--;
             }
         } else {
             if (s.done_valid) (void)hipEventSynchronize(s.done);
             (void)hipEventSynchronize(s.ready);
             slab_free(s);
+            ctx->slabs_owned--;
         }
     }
     delete plan;

@@ -185,6 +185,7 @@ def test_permute_and_attention_validation_without_a_device(host_ctx):
     assert f(h, plan.handle, bad, t, t, a, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.INVALID_ARGUMENT
     assert f(h, plan.handle, t, t, t, a, 0, 4, 0, 2, 1, 0.0, t, lse, None) == fx.PLAN_MISMATCH
     assert f(h, plan.handle, t, t, t, a, 0, 2, 0, 2, 0, 0.0, t, lse, None) == fx.PLAN_MISMATCH
-    assert f(h, plan.handle, t, t, t, None, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.INVALID_ARGUMENT
+    assert f(h, plan.handle, t, t, t, None, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.NO_DEVICE  # cu_seqlens_dev may be NULL: the plan has the lengths
+    assert f(h, plan.handle, t, t, t, a, 0, 2, 0, 2, 1, 0.0, t, None, None) == fx.INVALID_ARGUMENT      # lse is required
     assert f(h, None, t, t, t, a, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.INVALID_ARGUMENT
     plan.close()

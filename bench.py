@@ -40,7 +40,10 @@ HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 # each scaled by what the same counter reads for a plain copy of known size; the commands, the raw
 # counter values and the algorithmic bytes beside them are in profiles/attention_hbm_traffic.md).
 # bench.py cannot run the profiler on itself: these are the figures of that summary.
-MEASURED_HBM_TRAFFIC = {}
+MEASURED_HBM_TRAFFIC = {
+    ("pareto-64k", "fwd"): 1313768630, ("pareto-64k", "bwd_dq"): 1623344037, ("pareto-64k", "bwd_dkv"): 1842422372,
+    ("single-128k", "fwd"): 42790452858, ("single-128k", "bwd_dq"): 73218150768, ("single-128k", "bwd_dkv"): 22220939311,
+}
 
 
 def permute_leg(ctx, fx, wl, torch, stream):

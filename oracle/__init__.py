@@ -51,7 +51,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(str(_LIB))
         for name in ("flexsp_oracle_attn", "flexsp_oracle_rows", "flexsp_oracle_dkv_rows",
-                     "flexsp_oracle_pack", "flexsp_oracle_unpack"):
+                     "flexsp_oracle_attn_kvshard", "flexsp_oracle_pack", "flexsp_oracle_unpack"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -147,6 +147,51 @@ def dkv_rows(q, k, v, dO, cu, tasks, causal=True, scale=None):
     if rc:
         raise ValueError("oracle: bad arguments")
     return dK, dV
+
+
+def attn_fwd_kvshard(q, k, v, cu_q, cu_k, shift, causal=True, scale=None):
+    """Attention of each sequence's queries against one shard of its keys (context parallelism,
+    paper Sec. 2.1.3, paragraph "Context Parallelism", and the appendix on integrating it): q [Tq,Hq,D]; k, v [Tk,Hkv,D] hold the shard;
+    shard key j of sequence b is visible to its query i iff not causal or j <= i + shift[b].
+    Returns (O [Tq,Hq,D], LSE [Hq,Tq]); a row that sees no key has O = 0 and LSE = -inf."""
+    q, dt = _in(q)
+    k, dk = _in(k)
+    v, dv = _in(v)
+    assert dt == dk == dv
+    cu_q = np.ascontiguousarray(cu_q, dtype=np.int32)
+    cu_k = np.ascontiguousarray(cu_k, dtype=np.int32)
+    shift = np.ascontiguousarray(shift, dtype=np.int32)
+    Tq, Hq, D = q.shape
+    Tk, Hkv, Dk = k.shape
+    assert v.shape == k.shape and Dk == D and cu_q[-1] == Tq and cu_k[-1] == Tk
+    assert len(cu_q) == len(cu_k) == len(shift) + 1
+    scale = 1.0 / np.sqrt(D) if scale is None else float(scale)
+    O = np.zeros((Tq, Hq, D)); LSE = np.zeros((Hq, Tq))
+    rc = _load().flexsp_oracle_attn_kvshard(_p(q), _p(k), _p(v), dt, _p(cu_q), _p(cu_k), _p(shift), len(shift), Hq,
+                                            Hkv, D, int(bool(causal)), ctypes.c_double(scale), _p(O), _p(LSE))
+    if rc:
+        raise ValueError("oracle: bad arguments")
+    return O, LSE
+
+
+def lse_merge(o_a, lse_a, o_b, lse_b):
+    """Two partial attentions of the same queries over disjoint key sets -> attention over the union:
+    softmax weights of the union are the partial ones rescaled by exp(LSE_part - LSE_union).
+    o [T,H,D], lse [H,T], fp64.  A part with LSE = -inf (no key) has weight 0; both: O = 0, LSE = -inf."""
+    o_a, o_b = np.asarray(o_a, dtype=np.float64), np.asarray(o_b, dtype=np.float64)
+    lse_a, lse_b = np.asarray(lse_a, dtype=np.float64), np.asarray(lse_b, dtype=np.float64)
+    T, H, D = o_a.shape
+    out = np.zeros((T, H, D)); lse = np.full((H, T), -np.inf)
+    for t in range(T):
+        for h in range(H):
+            la, lb = lse_a[h, t], lse_b[h, t]
+            m = max(la, lb)
+            if m == -np.inf:
+                continue
+            wa, wb = np.exp(la - m), np.exp(lb - m)
+            out[t, h] = (wa * o_a[t, h] + wb * o_b[t, h]) / (wa + wb)
+            lse[h, t] = m + np.log(wa + wb)
+    return out, lse
 
 
 def pack(x, P):

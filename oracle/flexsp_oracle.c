@@ -335,6 +335,62 @@ int flexsp_oracle_dkv_rows(const void *q, const void *k, const void *v, const vo
     return failed ? -1 : 0;
 }
 
+/*
+ * Attention of each sequence's queries against ONE SHARD of its keys, the unit of work of context
+ * parallelism (paper Sec. 2.1.3, paragraph "Context Parallelism": queries, keys and values are split along
+ * the sequence, key/value chunks travel round a ring, and attention is computed chunk by chunk;
+ * the appendix on integrating context parallelism).  Sequence b has queries at rows
+ * cu_q[b] .. cu_q[b+1]-1 of q and shard keys at rows cu_k[b] .. cu_k[b+1]-1 of k and v.  With
+ * causal masking, shard key j is visible to query i iff j <= i + shift[b], where shift[b] =
+ * (position of the first query in its sequence) - (position of the shard's first key); without,
+ * every shard key is visible.  Per row: softmax over the visible shard keys only,
+ *   O_i = sum_j P_ij v_j,  LSE_i = log sum_j exp(S_ij);   no visible key: O_i = 0, LSE_i = -inf.
+ * The visible keys of a row are always a prefix 0 .. n-1 of the shard, so a row is evaluated by
+ * row_forward as the last row of a causal problem over that prefix: no new arithmetic.
+ * O [Tq, Hq, D], LSE [Hq, Tq], fp64.
+ */
+int flexsp_oracle_attn_kvshard(const void *q, const void *k, const void *v, int dtype, const int32_t *cu_q,
+                               const int32_t *cu_k, const int32_t *shift, int B, int Hq, int Hkv, int D,
+                               int causal, double scale, double *O, double *LSE)
+{
+    if (check_dims(B, Hq, Hkv, D, cu_q) || check_dims(B, Hq, Hkv, D, cu_k)) return -1;
+    int G = Hq / Hkv;
+    int64_t Tq = cu_q[B];
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < B; b++) {
+        for (int g = 0; g < Hkv; g++) {
+            int64_t tq0 = cu_q[b], tk0 = cu_k[b];
+            int sq = cu_q[b + 1] - cu_q[b], sk = cu_k[b + 1] - cu_k[b];
+            if (sq == 0) continue;
+            scratch_t w;
+            int m = sk > sq ? sk : sq;
+            if (scratch_alloc(&w, m, D)) { failed = 1; scratch_free(&w); continue; }
+            gather(k, dtype, tk0, sk, Hkv, g, D, w.k);
+            gather(v, dtype, tk0, sk, Hkv, g, D, w.v);
+            transpose(w.k, sk, D, w.kt);
+            for (int hh = 0; hh < G; hh++) {
+                int h = g * G + hh;
+                gather(q, dtype, tq0, sq, Hq, h, D, w.q);
+                for (int i = 0; i < sq; i++) {
+                    int64_t n = causal ? (int64_t)i + shift[b] + 1 : sk; /* visible keys: 0 .. n-1 */
+                    if (n > sk) n = sk;
+                    double *oi = O + ((tq0 + i) * Hq + h) * D;
+                    double *li = &LSE[(int64_t)h * Tq + tq0 + i];
+                    if (n <= 0) {
+                        for (int d = 0; d < D; d++) oi[d] = 0.0;
+                        *li = -INFINITY;
+                        continue;
+                    }
+                    row_forward(w.q + (int64_t)i * D, w.kt, w.v, sk, D, (int)n - 1, 1, scale, w.p, oi, li);
+                }
+            }
+            scratch_free(&w);
+        }
+    }
+    return failed ? -1 : 0;
+}
+
 /* Layout permute on raw elements of `eb` bytes each.  Requires H % P == 0. */
 int flexsp_oracle_pack(const void *src, void *dst, int64_t T, int H, int D, int P, int eb)
 {

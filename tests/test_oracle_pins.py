@@ -459,3 +459,89 @@ def test_workload_recipes():
     assert wl.f32_to_bf16_bits(x).tolist() == [0x3F80, 0x3F80, 0x3F82, 0xC020, 0x7F62]
     a = wl.normal_bf16(5, 1, (1000,)); b = wl.normal_bf16(5, 1, (1000,))
     assert np.array_equal(a, b) and abs(wl.bf16_bits_to_f32(a).std() - 1) < 0.1
+
+
+# ----------------------------------------------------------------------------- key shards (context parallelism)
+def _shard_inputs(lens, Hq, Hkv, D, seed):
+    T = sum(lens)
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((T, Hq, D)), rng.standard_normal((T, Hkv, D)), rng.standard_normal((T, Hkv, D)))
+
+
+def _split(x, cu, lo, hi):
+    """rows lo[b] .. hi[b]-1 of every sequence, concatenated; and their prefix sums"""
+    parts = [x[int(cu[b]) + lo[b]: int(cu[b]) + hi[b]] for b in range(len(lo))]
+    n = [hi[b] - lo[b] for b in range(len(lo))]
+    return np.concatenate(parts) if parts else x[:0], wl.cu_seqlens(n)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_kvshard_parts_merge_into_the_full_attention(causal):
+    """Attention over ALL keys (the function pinned above) = the attentions over two or three key
+    shards merged by their log-sum-exps; also for a chunk of the queries only, as a device of a
+    context-parallel group holds them.  Pins attn_fwd_kvshard and lse_merge together against
+    attn_fwd: a wrong mask offset, a wrong weight or a lost normaliser breaks the identity."""
+    lens, Hq, Hkv, D = [9, 1, 40, 17, 64], 4, 2, 8
+    cu = wl.cu_seqlens(lens)
+    q, k, v = _shard_inputs(lens, Hq, Hkv, D, 31)
+    O, LSE = oracle.attn_fwd(q, k, v, cu, causal)
+    rng = np.random.default_rng(32)
+    for trial in range(4):
+        c1 = [int(rng.integers(0, s + 1)) for s in lens]                  # first cut: may be 0 or s (an empty shard)
+        c2 = [int(rng.integers(c, s + 1)) for c, s in zip(c1, lens)]
+        a0 = [int(rng.integers(0, s)) for s in lens]                       # the query chunk starts here ...
+        a1 = [int(rng.integers(a + 1, s + 1)) for a, s in zip(a0, lens)]   # ... and ends here
+        if trial == 0:
+            a0, a1 = [0] * len(lens), list(lens)                           # all queries
+        qs, cu_q = _split(q, cu, a0, a1)
+        parts = []
+        for lo, hi in (([0] * len(lens), c1), (c1, c2), (c2, list(lens))):
+            ks, cu_k = _split(k, cu, lo, hi)
+            vs, _ = _split(v, cu, lo, hi)
+            shift = [a - l for a, l in zip(a0, lo)]                        # first query position - first key position
+            parts.append(oracle.attn_fwd_kvshard(qs, ks, vs, cu_q, cu_k, shift, causal))
+        o12, l12 = oracle.lse_merge(parts[0][0], parts[0][1], parts[1][0], parts[1][1])
+        o, l = oracle.lse_merge(o12, l12, parts[2][0], parts[2][1])
+        o_alt, l_alt = oracle.lse_merge(parts[0][0], parts[0][1],
+                                        *oracle.lse_merge(parts[1][0], parts[1][1], parts[2][0], parts[2][1]))
+        Oq, _ = _split(O, cu, a0, a1)
+        Lq = np.concatenate([LSE[:, int(cu[b]) + a0[b]: int(cu[b]) + a1[b]] for b in range(len(lens))], axis=1)
+        assert np.abs(o - Oq).max() < 1e-12 and np.abs(l - Lq).max() < 1e-12
+        assert np.abs(o_alt - Oq).max() < 1e-12 and np.abs(l_alt - Lq).max() < 1e-12     # merge order is free
+
+
+def test_kvshard_dense_brute_force_and_closed_forms():
+    """(1) Textbook masked softmax over a dense score matrix with the mask j <= i + shift written out.
+    (2) q = 0: every visible key weighs the same, so O = mean of the visible V rows, LSE = ln(count).
+    (3) Rows that see no key: O = 0, LSE = -inf, and merging them with anything returns the other part."""
+    sq, sk, Hq, Hkv, D = 11, 14, 2, 1, 4
+    rng = np.random.default_rng(41)
+    q, k, v = rng.standard_normal((sq, Hq, D)), rng.standard_normal((sk, Hkv, D)), rng.standard_normal((sk, Hkv, D))
+    cu_q, cu_k = wl.cu_seqlens([sq]), wl.cu_seqlens([sk])
+    for shift in (-5, -1, 0, 3, 20):
+        O, L = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, [shift], True)
+        for h in range(Hq):
+            S = (q[:, h] @ k[:, 0].T) / np.sqrt(D)
+            vis = np.arange(sk)[None, :] <= np.arange(sq)[:, None] + shift
+            E = np.where(vis, np.exp(S), 0.0)
+            Z = E.sum(1)
+            ref = np.where(Z[:, None] > 0, (E @ v[:, 0]) / np.where(Z > 0, Z, 1.0)[:, None], 0.0)
+            assert np.abs(O[:, h] - ref).max() < 1e-12
+            assert np.abs(L[h][Z > 0] - np.log(Z[Z > 0])).max(initial=0.0) < 1e-12
+            assert (np.isneginf(L[h]) == (Z == 0)).all() and (O[:, h][Z == 0] == 0).all()
+        O0, L0 = oracle.attn_fwd_kvshard(np.zeros_like(q), k, v, cu_q, cu_k, [shift], True)
+        for i in range(sq):
+            n = min(max(i + shift + 1, 0), sk)
+            if n > 0:
+                assert np.abs(O0[i, 0] - v[:n, 0].mean(0)).max() < 1e-13 and abs(L0[0, i] - np.log(n)) < 1e-13
+    # not causal: the shift is ignored, every key of the shard counts
+    On, Ln = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, [-100], False)
+    Of, Lf = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, [100], True)
+    assert np.array_equal(On, Of) and np.array_equal(Ln, Lf)
+    # a part without keys is the neutral element of the merge
+    Oe, Le = oracle.attn_fwd_kvshard(q, k[:0], v[:0], cu_q, wl.cu_seqlens([0]), [0], True)
+    assert not Oe.any() and np.isneginf(Le).all()
+    Om, Lm = oracle.lse_merge(Oe, Le, On, Ln)
+    assert np.array_equal(Om, On) and np.array_equal(Lm, Ln)
+    Om, Lm = oracle.lse_merge(Oe, Le, Oe, Le)
+    assert not Om.any() and np.isneginf(Lm).all()

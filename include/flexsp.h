@@ -220,6 +220,45 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
                            flexsp_tensor dv, int32_t grad_dtype, flexsp_stream stream);
 
 /*
+ * Attention against ONE SHARD of the keys, and the merge of such partial results: the per-device
+ * work of context parallelism (Sec. 2.1.3, paragraph "Context Parallelism": queries, keys and values
+ * are split along the sequence, key/value chunks travel round a ring and attention is computed chunk
+ * by chunk; the appendix on integrating context parallelism into FlexSP).  Forward only.
+ *
+ * flexsp_plan_create_kvshard - tile plan for B sequences whose QUERIES are rows cu_q[b] .. cu_q[b+1]-1
+ *   of q / o / lse and whose shard KEYS are rows cu_k[b] .. cu_k[b+1]-1 of k / v (host pointers, B+1
+ *   int32 prefix sums each; either side may be empty for a sequence).  shift_host[b] (B int32,
+ *   |shift| <= 2^30) = position of sequence b's first query inside the full sequence minus position of
+ *   the shard's first key: with `causal`, shard key j is visible to query row i iff j <= i + shift[b];
+ *   without, every shard key is visible and shift is ignored.  The plan serves
+ *   flexsp_attn_varlen_fwd_kvshard only (the other attention calls answer PLAN_MISMATCH); it is destroyed
+ *   by flexsp_plan_destroy and inspected by flexsp_plan_num_items / _get_items with FLEXSP_PASS_FWD, where
+ *   an item's seq_start holds the sequence INDEX b.
+ *
+ * flexsp_attn_varlen_fwd_kvshard - per query row, softmax over the visible shard keys only:
+ *   O = sum_j P_j v_j (bf16), LSE = log sum_j exp(scale q.k_j) (fp32, natural log, [head_count, Tq]).
+ *   A row that sees no key of the shard gets O = 0 and LSE = -inf.  Arguments as flexsp_attn_varlen_fwd.
+ *
+ * flexsp_lse_merge - two partial results of the same queries over DISJOINT key sets -> the result
+ *   over their union:  LSE = log(exp(lse_a) + exp(lse_b)),  O = exp(lse_a - LSE) O_a + exp(lse_b - LSE) O_b
+ *   (fp32 arithmetic, O rounded to bf16 once).  o_* are views of [T, H, D] bf16 (the H heads start at each
+ *   view's ptr), lse_* fp32 [H, T] contiguous; D is 64 or 128.  A part with LSE = -inf counts nothing,
+ *   whatever its O holds; both -inf: O = 0, LSE = -inf.  o_out / lse_out may be the very same memory as
+ *   one of the inputs (merge in place), but must not overlap them otherwise.  Merging is associative up
+ *   to rounding, so shards can be folded in as they arrive.
+ * Errors: INVALID_ARGUMENT, UNSUPPORTED, PLAN_MISMATCH, NO_DEVICE, OUT_OF_MEMORY, HIP_ERROR.
+ */
+int flexsp_plan_create_kvshard(flexsp_ctx *ctx, const int32_t *cu_q_host, const int32_t *cu_k_host,
+                               const int32_t *shift_host, int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
+                               int causal, flexsp_plan **out);
+int flexsp_attn_varlen_fwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                                   flexsp_tensor v, int32_t head_begin, int32_t head_count, int32_t kv_head_begin,
+                                   int32_t kv_head_count, int causal, float softmax_scale, flexsp_tensor o,
+                                   float *lse, flexsp_stream stream);
+int flexsp_lse_merge(flexsp_ctx *ctx, flexsp_tensor o_a, const float *lse_a, flexsp_tensor o_b, const float *lse_b,
+                     flexsp_tensor o_out, float *lse_out, int64_t T, int32_t H, int32_t D, flexsp_stream stream);
+
+/*
  * The forward for callers that cannot allocate: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same result as flexsp_attn_varlen_fwd, bit for bit, but it takes
  * no plan and calls no hipMalloc, hipFree or any other allocating routine: the work queues are built

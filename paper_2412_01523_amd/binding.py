@@ -26,6 +26,7 @@ EXPORTS = (
     "flexsp_plan_tile_rows", "flexsp_attn_bwd_workspace_bytes",
     "flexsp_pack", "flexsp_unpack", "flexsp_pack_many", "flexsp_unpack_many",
     "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd", "flexsp_attn_varlen_fwd_static",
+    "flexsp_plan_create_kvshard", "flexsp_attn_varlen_fwd_kvshard", "flexsp_lse_merge",
     "flexsp_profile_start", "flexsp_profile_stop",
     "flexsp_bucket_dp", "flexsp_chunk_dp", "flexsp_min_microbatches",
 )
@@ -103,6 +104,12 @@ def lib() -> ctypes.CDLL:
         L.flexsp_attn_varlen_fwd_static.argtypes = [c_void_p, Tensor, Tensor, Tensor, c_void_p, c_int32, c_int64,
                                                     c_int32, c_int32, c_int32, c_int32, c_int32, c_int, c_float,
                                                     Tensor, c_void_p, c_void_p]
+        L.flexsp_plan_create_kvshard.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_int32,
+                                                 c_int32, c_int, POINTER(c_void_p)]
+        L.flexsp_attn_varlen_fwd_kvshard.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, c_int32, c_int32,
+                                                     c_int32, c_int32, c_int, c_float, Tensor, c_void_p, c_void_p]
+        L.flexsp_lse_merge.argtypes = [c_void_p, Tensor, c_void_p, Tensor, c_void_p, Tensor, c_void_p, c_int64,
+                                       c_int32, c_int32, c_void_p]
         L.flexsp_bucket_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int32), c_void_p,
                                        POINTER(c_int64)]
         L.flexsp_chunk_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int64)]
@@ -219,6 +226,23 @@ class Plan:
             pass
 
 
+class ShardPlan(Plan):
+    """flexsp_plan for attention against one shard of the keys (flexsp_plan_create_kvshard)."""
+
+    def __init__(self, ctx: Context, cu_q_host, cu_k_host, shift_host, hq: int, hkv: int, d: int, causal: bool = True):
+        cu_q = np.ascontiguousarray(cu_q_host, dtype=np.int32)
+        cu_k = np.ascontiguousarray(cu_k_host, dtype=np.int32)
+        shift = np.ascontiguousarray(shift_host, dtype=np.int32)
+        assert cu_q.ndim == 1 and len(cu_q) == len(cu_k) == len(shift) + 1
+        self.ctx = ctx
+        self.handle = c_void_p()
+        self.cu, self.cu_k, self.shift = cu_q, cu_k, shift
+        self.hq, self.hkv, self.d, self.causal = hq, hkv, d, bool(causal)
+        _check(lib().flexsp_plan_create_kvshard(ctx.handle, cu_q.ctypes.data_as(c_void_p), cu_k.ctypes.data_as(c_void_p),
+                                                shift.ctypes.data_as(c_void_p), len(shift), hq, hkv, d,
+                                                int(bool(causal)), byref(self.handle)), "flexsp_plan_create_kvshard")
+
+
 def flexsp_pack(ctx: Context, src, dst, P: int, stream=None):
     """src [T,H,D] -> dst [P,T,H/P,D] (dense torch tensors on the context's GPU)."""
     T, H, D = src.shape
@@ -268,7 +292,8 @@ def flexsp_attn_varlen_fwd(ctx: Context, plan: Plan, q, k, v, cu_seqlens_dev, o,
     head_count = plan.hq if head_count is None else head_count
     kv_head_count = plan.hkv if kv_head_count is None else kv_head_count
     _check(lib().flexsp_attn_varlen_fwd(ctx.handle, plan.handle, _view(q), _view(k), _view(v),
-                                        cu_seqlens_dev.data_ptr(), head_begin, head_count, kv_head_begin,
+                                        None if cu_seqlens_dev is None else cu_seqlens_dev.data_ptr(), head_begin,
+                                        head_count, kv_head_begin,
                                         kv_head_count, int(bool(causal)), float(softmax_scale), _view(o),
                                         lse.data_ptr(), _stream(stream)), "flexsp_attn_varlen_fwd")
 
@@ -281,10 +306,30 @@ def flexsp_attn_varlen_bwd(ctx: Context, plan: Plan, q, k, v, o, dO, lse, cu_seq
     assert dq.element_size() == dk.element_size() == dv.element_size()
     grad_dtype = F32 if dq.element_size() == 4 else BF16      # gradient tensors are bf16 or fp32
     _check(lib().flexsp_attn_varlen_bwd(ctx.handle, plan.handle, _view(q), _view(k), _view(v), _view(o),
-                                        _view(dO), lse.data_ptr(), cu_seqlens_dev.data_ptr(), head_begin,
+                                        _view(dO), lse.data_ptr(),
+                                        None if cu_seqlens_dev is None else cu_seqlens_dev.data_ptr(), head_begin,
                                         head_count, kv_head_begin, kv_head_count, int(bool(causal)),
                                         float(softmax_scale), _view(dq), _view(dk), _view(dv),
                                         grad_dtype, _stream(stream)), "flexsp_attn_varlen_bwd")
+
+
+def flexsp_attn_varlen_fwd_kvshard(ctx: Context, plan: ShardPlan, q, k, v, o, lse, *, head_begin=0, head_count=None,
+                                   kv_head_begin=0, kv_head_count=None, causal=True, softmax_scale=0.0, stream=None):
+    head_count = plan.hq if head_count is None else head_count
+    kv_head_count = plan.hkv if kv_head_count is None else kv_head_count
+    _check(lib().flexsp_attn_varlen_fwd_kvshard(ctx.handle, plan.handle, _view(q), _view(k), _view(v), head_begin,
+                                                head_count, kv_head_begin, kv_head_count, int(bool(causal)),
+                                                float(softmax_scale), _view(o), lse.data_ptr(), _stream(stream)),
+           "flexsp_attn_varlen_fwd_kvshard")
+
+
+def flexsp_lse_merge(ctx: Context, o_a, lse_a, o_b, lse_b, o_out, lse_out, stream=None):
+    """o_* [T,H,D] bf16 views, lse_* [H,T] fp32 contiguous; o_out / lse_out may be one of the inputs."""
+    T, H, D = o_a.shape
+    assert o_b.shape == o_a.shape == o_out.shape and lse_a.shape == lse_b.shape == lse_out.shape == (H, T)
+    assert lse_a.is_contiguous() and lse_b.is_contiguous() and lse_out.is_contiguous()
+    _check(lib().flexsp_lse_merge(ctx.handle, _view(o_a), lse_a.data_ptr(), _view(o_b), lse_b.data_ptr(), _view(o_out),
+                                  lse_out.data_ptr(), T, H, D, _stream(stream)), "flexsp_lse_merge")
 
 
 def flexsp_attn_varlen_fwd_static(ctx: Context, q, k, v, cu_seqlens_dev, o, lse, *, head_begin=0, head_count=None,

@@ -19,7 +19,8 @@ INCLUDE = PKG.parent / "include"
 OBJ = CSRC / "_build"
 LIB = PKG / "libflexsp.so"
 
-SOURCES = ["flexsp_host.hip", "pack.hip", "attn_fwd.hip", "attn_bwd.hip", "planner.hip", "fwd_static.hip"]
+SOURCES = ["flexsp_host.hip", "pack.hip", "attn_fwd.hip", "attn_bwd.hip", "planner.hip", "fwd_static.hip",
+           "lse_merge.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

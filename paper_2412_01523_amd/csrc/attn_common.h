@@ -339,6 +339,21 @@ __device__ __forceinline__ flexsp_item load_item(const flexsp_item *items, int i
     return it;
 }
 
+__device__ __forceinline__ flexsp_shard_item load_shard_item(const flexsp_shard_item *items, int idx)
+{
+    const flexsp_shard_item v = items[idx];
+    flexsp_shard_item it;
+    it.q_start = __builtin_amdgcn_readfirstlane(v.q_start);
+    it.q_len = __builtin_amdgcn_readfirstlane(v.q_len);
+    it.k_start = __builtin_amdgcn_readfirstlane(v.k_start);
+    it.k_len = __builtin_amdgcn_readfirstlane(v.k_len);
+    it.shift = __builtin_amdgcn_readfirstlane(v.shift);
+    it.tile = __builtin_amdgcn_readfirstlane(v.tile);
+    it.head = __builtin_amdgcn_readfirstlane(v.head);
+    it.pad = 0;
+    return it;
+}
+
 // Work distribution.  The plan holds one longest-first item list per XCD, balanced on the host.
 // Workgroup w runs on XCD w % nq (workgroups are dispatched round-robin over the XCDs); that
 // list is its home queue, and it is the (w / nq)-th of the W workgroups there.  Items are handed

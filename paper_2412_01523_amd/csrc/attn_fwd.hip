@@ -31,7 +31,12 @@ namespace {
 template <int V>
 using ic = std::integral_constant<int, V>;
 
-template <int D>
+// SHARD = true is the variant for one shard of the keys (context parallelism): a work item then
+// names separate query and key ranges and an offset `shift` between their positions, key j is
+// visible to query row i iff j <= i + shift (when causal), rows may see no key at all (O = 0,
+// LSE = -inf), and up to three 32-key blocks of a wavefront need masking (the diagonal crosses two
+// when shift is not a multiple of 32, plus the ragged end of the shard).
+template <int D, bool SHARD>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
 {
     typedef LdsTile<D> L;
@@ -55,35 +60,60 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     int item = deal.first(a.pq, &deal_word, wave, lane0);
     for (; item >= 0; item = deal.advance()) {
         deal.prefetch();
-        const flexsp_item it = load_item(a.pq.items, item);
+        // s: query rows of the sequence; sk: its keys; tok0 / ktok0: their first rows in q / k, v
+        int s, sk, shift, h, q0;
+        int64_t tok0, ktok0;
+        if constexpr (SHARD) {
+            const flexsp_shard_item it = load_shard_item((const flexsp_shard_item *)a.pq.items, item);
+            s = it.q_len; sk = it.k_len; shift = it.shift; h = it.head; q0 = it.tile * kFwdBq;
+            tok0 = it.q_start; ktok0 = it.k_start;
+        } else {
+            const flexsp_item it = load_item(a.pq.items, item);
+            s = it.seq_len; sk = s; shift = 0; h = it.head; q0 = it.tile * kFwdBq;
+            tok0 = it.seq_start; ktok0 = tok0;
+        }
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
         int lane = lane0;
         asm volatile("" : "+v"(lane));
         const int r = lane & 31, hl = lane >> 5;
-        const int s = it.seq_len, h = it.head, g = h / a.G;
-        const int q0 = it.tile * kFwdBq;
-        const int64_t tok0 = it.seq_start;
-        const int kv_end = a.causal ? min(s, q0 + kFwdBq) : s;  // keys this item needs
+        const int g = h / a.G;
+        // keys this item needs
+        const int kv_end = SHARD ? (a.causal ? max(0, min(sk, q0 + kFwdBq + shift)) : sk)
+                                 : (a.causal ? min(s, q0 + kFwdBq) : s);
+        if constexpr (SHARD) {
+            if (kv_end <= 0) {
+                // no row of this item sees a key of the shard: O = 0, LSE = -inf (the neutral element
+                // of the merge); deal.advance() holds the barrier every item ends with
+                for (int idx = tid; idx < kFwdBq * L::CH; idx += kThreads) {
+                    const int row = q0 + idx / L::CH;
+                    if (row < s)
+                        *(u32x4 *)(a.out_o + (tok0 + row) * a.o_st + (int64_t)h * a.o_sh + (idx % L::CH) * 8) =
+                            u32x4{0, 0, 0, 0};
+                }
+                if (tid < kFwdBq && q0 + tid < s) a.lse_out[(int64_t)h * a.T + tok0 + q0 + tid] = -INFINITY;
+                continue;
+            }
+        }
         const int ntiles = (kv_end + kFwdBk - 1) / kFwdBk;
-        const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
-        const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
+        const uint16_t *kbase = a.k + ktok0 * a.k_st + (int64_t)g * a.k_sh;
+        const uint16_t *vbase = a.v + ktok0 * a.v_st + (int64_t)g * a.v_sh;
 
         const uint32_t goffk = tile_goff<D>(a.k_st, wave, lane), goffv = tile_goff<D>(a.v_st, wave, lane);
         // whole-tile copies (all of this wavefront's copy instructions back to back)
         auto prefetch_k = [&](int t, int buf) {
             char *dst = smem + buf * TILE;
-            if ((t + 1) * kFwdBk <= s)  // whole tile inside the sequence
+            if ((t + 1) * kFwdBk <= sk)  // whole tile inside the sequence
                 load_tile_async_fast<D, kFwdBk>(dst, kbase + (int64_t)t * kFwdBk * a.k_st, a.k_st, goffk, wave);
             else
-                load_tile_async<D, kFwdBk>(dst, kbase, a.k_st, t * kFwdBk, s - 1, wave, lane);
+                load_tile_async<D, kFwdBk>(dst, kbase, a.k_st, t * kFwdBk, sk - 1, wave, lane);
         };
         auto prefetch_v = [&](int t, int buf) {
             char *dst = smem + (2 + buf) * TILE;
-            if ((t + 1) * kFwdBk <= s)
+            if ((t + 1) * kFwdBk <= sk)
                 load_tile_async_fast<D, kFwdBk>(dst, vbase + (int64_t)t * kFwdBk * a.v_st, a.v_st, goffv, wave);
             else
-                load_tile_async<D, kFwdBk>(dst, vbase, a.v_st, t * kFwdBk, s - 1, wave, lane);
+                load_tile_async<D, kFwdBk>(dst, vbase, a.v_st, t * kFwdBk, sk - 1, wave, lane);
         };
         prefetch_k(0, 0);
 
@@ -102,16 +132,26 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             }
         }
         // last 32-key block this wavefront has to look at (-1: none, its rows lie past the sequence)
-        const int cmax = wq_lo >= s ? -1 : (a.causal ? min((kv_end - 1) >> 5, wq_lo >> 5) : (kv_end - 1) >> 5);
-        const int cmask = a.causal ? (wq_lo >> 5) : ((s - 1) >> 5);  // the block that needs masking
-        const int lim = a.causal ? qrow : s - 1;                      // largest visible key of this lane's row
+        int cmax, cmask, lim;
+        if constexpr (SHARD) {
+            // (>> of a negative number rounds down: a diagonal left of the shard gives a negative block)
+            cmax = wq_lo >= s ? -1 : max(-1, a.causal ? min((kv_end - 1) >> 5, (wq_lo + 31 + shift) >> 5) : (kv_end - 1) >> 5);
+            cmask = a.causal ? min((wq_lo + shift) >> 5, (sk - 1) >> 5) : ((sk - 1) >> 5);  // FIRST block that needs masking
+            lim = a.causal ? min(qrow + shift, sk - 1) : sk - 1;
+        } else {
+            cmax = wq_lo >= s ? -1 : (a.causal ? min((kv_end - 1) >> 5, wq_lo >> 5) : (kv_end - 1) >> 5);
+            cmask = a.causal ? (wq_lo >> 5) : ((s - 1) >> 5);  // the block that needs masking
+            lim = a.causal ? qrow : s - 1;                      // largest visible key of this lane's row
+        }
 
         f32x16 oacc[DB];
 #pragma unroll
         for (int db = 0; db < DB; db++)
 #pragma unroll
             for (int i = 0; i < 16; i++) oacc[db][i] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f;
+        // (SHARD: a finite floor instead of -inf, because a row may have every key of a block masked:
+        // its scores are -inf, and -inf minus a reference of -inf would not be a number)
+        float m_run = SHARD ? -1e30f : -INFINITY, l_run = 0.f;
         f32x16 sacc[2];     // S of block c in sacc[c & 1]
         uint32_t pk[2][8];  // P of block c (bf16 pairs) in pk[c & 1]
 
@@ -190,7 +230,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             float m_new = m_run, psum = 0.f;
             if (c <= cmax) {
                 f32x16 &sa = sacc[CP];
-                if (c == cmask) {
+                if (SHARD ? c >= cmask : c == cmask) {
 #pragma unroll
                     for (int i = 0; i < 16; i++) {
                         const int kv = c * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
@@ -323,7 +363,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             iter_slow(ic<0>{}, 2 * t + 2, sK + 32 * L::ROWB, sV + 32 * L::ROWB);
         };
         // windows [0, tsteady) are steady ones: t + 3 <= ntiles, (t + 3) * kFwdBk <= s, 2t + 3 <= cmax
-        const int tsteady = max(0, min(min(ntiles, s / kFwdBk) - 2, (cmax - 1) >> 1));
+        // (SHARD: and the blocks of a steady window lie before the first masked one)
+        const int tsteady = max(0, min(min(ntiles, sk / kFwdBk) - 2, ((SHARD ? min(cmax, cmask) : cmax) - 1) >> 1));
         int t = 0;
         for (; t + 1 < tsteady; t += 2) {
             window_steady(ic<0>{}, t);
@@ -339,7 +380,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         // and this wavefront is past that barrier, so every wavefront has reached it
         if (wq_lo < s)
             store_rowT_bf16_lds<DB>(smem + wave * (32 * L::ROWB), a.out_o + (tok0 + wq_lo) * a.o_st + (int64_t)h * a.o_sh,
-                                    a.o_st, min(32, s - wq_lo), oacc, 1.0f / l_tot, lane);
+                                    a.o_st, min(32, s - wq_lo), oacc,
+                                    (SHARD && !(l_tot > 0.f)) ? 0.f : 1.0f / l_tot, lane);
         // deal.advance() holds the barrier after which the LDS buffers are reused by the next item
     }
     deal.finish();
@@ -350,9 +392,18 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
 hipError_t launch_attn_fwd(const AttnArgs &a, int D, int grid, hipStream_t s)
 {
     if (D == 128)
-        hipLaunchKernelGGL(attn_fwd_kernel<128>, dim3(grid), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_fwd_kernel<128, false>), dim3(grid), dim3(kThreads), 0, s, a);
     else
-        hipLaunchKernelGGL(attn_fwd_kernel<64>, dim3(grid), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_fwd_kernel<64, false>), dim3(grid), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd_kvshard(const AttnArgs &a, int D, int grid, hipStream_t s)
+{
+    if (D == 128)
+        hipLaunchKernelGGL((attn_fwd_kernel<128, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else
+        hipLaunchKernelGGL((attn_fwd_kernel<64, true>), dim3(grid), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

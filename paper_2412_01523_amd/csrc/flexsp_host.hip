@@ -55,6 +55,10 @@ struct flexsp_plan {
     int32_t B, Hq, Hkv, D, causal;
     int64_t T;
     std::vector<int32_t> cu;
+    // key-shard plans (forward only): the shard's own boundaries and the position offsets
+    bool kvshard = false;
+    std::vector<int32_t> cu_k, shift;
+    int64_t Tk = 0;
     HostPass pass[3];
     // device side (null for host-only plans): one allocation, carved up
     void *dev_base;
@@ -185,6 +189,8 @@ struct Work {
     int32_t group;  // (sequence, head) group id
 };
 
+void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int tile_rows, HostPass &out);
+
 // Builds one pass: lists the items, spreads whole (sequence, head) groups over the queues
 // (largest group first onto the least loaded queue, so tiles that read the same K/V run on
 // one XCD and share its L2), then orders each queue by decreasing cost so that the long
@@ -231,6 +237,12 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
             group_cost.push_back(gc);
         }
     }
+    distribute(work, group_cost, nq, tile_rows, out);
+}
+
+// Spreads listed work over the queues and orders every queue longest first (see build_pass).
+void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int tile_rows, HostPass &out)
+{
     // groups -> queues
     std::vector<int32_t> order(group_cost.size());
     for (size_t i = 0; i < order.size(); i++) order[i] = (int32_t)i;
@@ -319,13 +331,92 @@ int check_attn_common(flexsp_ctx *ctx, flexsp_plan *plan, const int32_t *cu_dev,
 {
     (void)cu_dev;  // the plan carries the lengths; the device copy is not read by the plan-based calls
     if (!ctx || !plan) return FLEXSP_INVALID_ARGUMENT;
-    if (plan->ctx != ctx) return FLEXSP_PLAN_MISMATCH;
+    if (plan->ctx != ctx || plan->kvshard) return FLEXSP_PLAN_MISMATCH;
     if (head_begin < 0 || kv_head_begin < 0 || head_count <= 0 || kv_head_count <= 0)
         return FLEXSP_INVALID_ARGUMENT;
     if (head_count % kv_head_count != 0) return FLEXSP_INVALID_ARGUMENT;
     if (head_count != plan->Hq || kv_head_count != plan->Hkv || (causal != 0) != (plan->causal != 0))
         return FLEXSP_PLAN_MISMATCH;
     if (ctx->device < 0 || !plan->dev_base) return FLEXSP_NO_DEVICE;
+    return FLEXSP_OK;
+}
+
+// Puts a freshly built plan's queues on the device (nothing to do for a host-only context): one
+// slab, carved into [items x3][offsets x3][counters x3][delta, lse2].  Items of a key-shard plan are
+// written in their wider device form.  On failure the plan is deleted and a status returned.
+int plan_upload(flexsp_ctx *ctx, flexsp_plan *p)
+{
+    for (int i = 0; i < 3; i++) std::memset(&p->dq[i], 0, sizeof(PassQueues));
+    if (ctx->device < 0) return FLEXSP_OK;
+    const size_t item_bytes = p->kvshard ? sizeof(flexsp_shard_item) : sizeof(flexsp_item);
+    {
+
+        // one allocation: [items x3][offsets x3][counters x3][delta]
+        int nq = ctx->num_xcd;
+        size_t off = 0, item_off[3], offs_off[3], ctr_off[3];
+        auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
+        for (int i = 0; i < 3; i++) {
+            item_off[i] = off;
+            off = align(off + p->pass[i].items.size() * item_bytes);
+        }
+        for (int i = 0; i < 3; i++) {
+            offs_off[i] = off;
+            off = align(off + (nq + 1) * sizeof(int32_t));
+        }
+        for (int i = 0; i < 3; i++) {
+            ctr_off[i] = off;
+            off = align(off + (nq + 1) * sizeof(int32_t));
+        }
+        size_t head_bytes = off;
+        size_t delta_off = off;
+        off = align(off + p->delta_bytes + 512);  // the dK/dV kernel reads up to 63 floats past a row's end
+        hipError_t e = hipSetDevice(ctx->device);
+        if (e == hipSuccess) e = slab_get(ctx, off ? off : 256, head_bytes ? head_bytes : 256, p->slab);
+        if (e != hipSuccess) {
+            delete p;
+            return hip_fail(e);
+        }
+        p->dev_base = p->slab.dev;
+        p->dev_bytes = off;
+        char *stage = (char *)p->slab.host;
+        std::memset(stage, 0, head_bytes);  // also the ticket counters: every plan starts with them clear
+        for (int i = 0; i < 3; i++) {
+            if (p->kvshard) {
+                // the host list names a sequence by its index (seq_start); the device item carries its ranges
+                flexsp_shard_item *d = (flexsp_shard_item *)(stage + item_off[i]);
+                for (size_t n = 0; n < p->pass[i].items.size(); n++) {
+                    const flexsp_item &it = p->pass[i].items[n];
+                    const int b = it.seq_start;
+                    d[n] = flexsp_shard_item{p->cu[b], p->cu[b + 1] - p->cu[b], p->cu_k[b], p->cu_k[b + 1] - p->cu_k[b],
+                                             p->shift[b], it.tile, it.head, 0};
+                }
+            } else if (!p->pass[i].items.empty()) {
+                std::memcpy(stage + item_off[i], p->pass[i].items.data(),
+                            p->pass[i].items.size() * sizeof(flexsp_item));
+            }
+            int32_t *o = (int32_t *)(stage + offs_off[i]);
+            for (int x = 0; x <= nq; x++) o[x] = (int32_t)p->pass[i].offsets[x];
+            p->dq[i].items = (const flexsp_item *)((char *)p->dev_base + item_off[i]);
+            p->dq[i].offsets = (const int32_t *)((char *)p->dev_base + offs_off[i]);
+            p->dq[i].counters = (int32_t *)((char *)p->dev_base + ctr_off[i]);
+            p->dq[i].nq = nq;
+        }
+        // asynchronous upload on the context's own stream, after the kernels of the slab's previous
+        // plan; the hot calls make their stream wait for `ready` (or find it complete already)
+        if (p->slab.done_valid) e = hipStreamWaitEvent(ctx->upload, p->slab.done, 0);
+        if (e == hipSuccess && head_bytes)
+            e = hipMemcpyAsync(p->dev_base, stage, head_bytes, hipMemcpyHostToDevice, ctx->upload);
+        if (e == hipSuccess) e = hipEventRecord(p->slab.ready, ctx->upload);
+        if (e != hipSuccess) {
+            (void)hipStreamSynchronize(ctx->upload);
+            slab_free(p->slab);
+            ctx->slabs_owned--;
+            delete p;
+            return hip_fail(e);
+        }
+        p->slab.done_valid = false;
+        p->delta = (float *)((char *)p->dev_base + delta_off);
+    }
     return FLEXSP_OK;
 }
 
@@ -508,63 +599,80 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
         delete p;
         return FLEXSP_OUT_OF_MEMORY;
     }
-    for (int i = 0; i < 3; i++) std::memset(&p->dq[i], 0, sizeof(PassQueues));
-    if (ctx->device >= 0) {
-        // one allocation: [items x3][offsets x3][counters x3][delta]
-        int nq = ctx->num_xcd;
-        size_t off = 0, item_off[3], offs_off[3], ctr_off[3];
-        auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
-        for (int i = 0; i < 3; i++) {
-            item_off[i] = off;
-            off = align(off + p->pass[i].items.size() * sizeof(flexsp_item));
+    {
+        int rc = plan_upload(ctx, p);
+        if (rc) return rc;
+    }
+    *out = p;
+    return FLEXSP_OK;
+}
+
+int flexsp_plan_create_kvshard(flexsp_ctx *ctx, const int32_t *cu_q, const int32_t *cu_k, const int32_t *shift,
+                               int32_t B, int32_t Hq, int32_t Hkv, int32_t D, int causal, flexsp_plan **out)
+{
+    if (!out) return FLEXSP_INVALID_ARGUMENT;
+    *out = nullptr;
+    if (!ctx || !cu_q || !cu_k || (!shift && B > 0) || B < 0 || Hq <= 0 || Hkv <= 0 || D <= 0)
+        return FLEXSP_INVALID_ARGUMENT;
+    if (Hq % Hkv != 0 || cu_q[0] != 0 || cu_k[0] != 0) return FLEXSP_INVALID_ARGUMENT;
+    for (int b = 0; b < B; b++) {
+        if (cu_q[b + 1] < cu_q[b] || cu_k[b + 1] < cu_k[b]) return FLEXSP_INVALID_ARGUMENT;
+        // positions are token counts: |shift| beyond 2^30 would overflow the kernels' 32-bit arithmetic
+        if (shift[b] > (1 << 30) || shift[b] < -(1 << 30)) return FLEXSP_INVALID_ARGUMENT;
+    }
+    if (D != 64 && D != 128) return FLEXSP_UNSUPPORTED;
+    flexsp_plan *p = new (std::nothrow) flexsp_plan;
+    if (!p) return FLEXSP_OUT_OF_MEMORY;
+    p->ctx = ctx;
+    p->B = B; p->Hq = Hq; p->Hkv = Hkv; p->D = D; p->causal = causal ? 1 : 0;
+    p->T = cu_q[B];
+    p->Tk = cu_k[B];
+    p->kvshard = true;
+    p->dev_base = nullptr; p->dev_bytes = 0; p->delta = nullptr;
+    p->uploaded = false; p->used = false; p->multi_stream = false; p->last_stream = nullptr;
+    p->delta_bytes = 0;  // forward only: no backward scratch
+    try {
+        p->cu.assign(cu_q, cu_q + B + 1);
+        p->cu_k.assign(cu_k, cu_k + B + 1);
+        p->shift.assign(shift, shift + B);
+        // items: (sequence index, query tile, head); cost = key tiles the tile's rows can see
+        std::vector<Work> work;
+        std::vector<int64_t> group_cost;
+        for (int b = 0; b < B; b++) {
+            const int32_t sq = cu_q[b + 1] - cu_q[b], sk = cu_k[b + 1] - cu_k[b];
+            if (sq <= 0) continue;
+            const int32_t nt = (int32_t)cdiv(sq, kFwdBq);
+            for (int h = 0; h < Hq; h++) {
+                const int32_t gid = (int32_t)group_cost.size();
+                int64_t gc = 0;
+                for (int32_t t = 0; t < nt; t++) {
+                    int64_t keys = sk;
+                    if (causal) keys = std::max<int64_t>(0, std::min<int64_t>(sk, (int64_t)(t + 1) * kFwdBq + shift[b]));
+                    Work w;
+                    w.it.seq_start = b;  // the sequence INDEX (see plan_upload); its ranges are in cu / cu_k / shift
+                    w.it.seq_len = sq;
+                    w.it.tile = t;
+                    w.it.head = h;
+                    w.cost = cdiv(keys, kFwdBk) + 1;  // an item without visible keys still writes its rows
+                    w.group = gid;
+                    work.push_back(w);
+                    gc += w.cost;
+                }
+                group_cost.push_back(gc);
+            }
         }
-        for (int i = 0; i < 3; i++) {
-            offs_off[i] = off;
-            off = align(off + (nq + 1) * sizeof(int32_t));
+        distribute(work, group_cost, ctx->num_xcd, kFwdBq, p->pass[FLEXSP_PASS_FWD]);
+        for (int i = 1; i < 3; i++) {
+            for (int x = 0; x <= kMaxQueues; x++) p->pass[i].offsets[x] = 0;
+            p->pass[i].tile_rows = 0;
         }
-        for (int i = 0; i < 3; i++) {
-            ctr_off[i] = off;
-            off = align(off + (nq + 1) * sizeof(int32_t));
-        }
-        size_t head_bytes = off;
-        size_t delta_off = off;
-        off = align(off + p->delta_bytes + 512);  // the dK/dV kernel reads up to 63 floats past a row's end
-        hipError_t e = hipSetDevice(ctx->device);
-        if (e == hipSuccess) e = slab_get(ctx, off ? off : 256, head_bytes ? head_bytes : 256, p->slab);
-        if (e != hipSuccess) {
-            delete p;
-            return hip_fail(e);
-        }
-        p->dev_base = p->slab.dev;
-        p->dev_bytes = off;
-        char *stage = (char *)p->slab.host;
-        std::memset(stage, 0, head_bytes);  // also the ticket counters: every plan starts with them clear
-        for (int i = 0; i < 3; i++) {
-            if (!p->pass[i].items.empty())
-                std::memcpy(stage + item_off[i], p->pass[i].items.data(),
-                            p->pass[i].items.size() * sizeof(flexsp_item));
-            int32_t *o = (int32_t *)(stage + offs_off[i]);
-            for (int x = 0; x <= nq; x++) o[x] = (int32_t)p->pass[i].offsets[x];
-            p->dq[i].items = (const flexsp_item *)((char *)p->dev_base + item_off[i]);
-            p->dq[i].offsets = (const int32_t *)((char *)p->dev_base + offs_off[i]);
-            p->dq[i].counters = (int32_t *)((char *)p->dev_base + ctr_off[i]);
-            p->dq[i].nq = nq;
-        }
-        // asynchronous upload on the context's own stream, after the kernels of the slab's previous
-        // plan; the hot calls make their stream wait for `ready` (or find it complete already)
-        if (p->slab.done_valid) e = hipStreamWaitEvent(ctx->upload, p->slab.done, 0);
-        if (e == hipSuccess && head_bytes)
-            e = hipMemcpyAsync(p->dev_base, stage, head_bytes, hipMemcpyHostToDevice, ctx->upload);
-        if (e == hipSuccess) e = hipEventRecord(p->slab.ready, ctx->upload);
-        if (e != hipSuccess) {
-            (void)hipStreamSynchronize(ctx->upload);
-            slab_free(p->slab);
-            ctx->slabs_owned--;
-            delete p;
-            return hip_fail(e);
-        }
-        p->slab.done_valid = false;
-        p->delta = (float *)((char *)p->dev_base + delta_off);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return FLEXSP_OUT_OF_MEMORY;
+    }
+    {
+        int rc = plan_upload(ctx, p);
+        if (rc) return rc;
     }
     *out = p;
     return FLEXSP_OK;
@@ -750,6 +858,66 @@ int flexsp_attn_varlen_fwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
         Timed tm(ctx, FLEXSP_K_FWD, (hipStream_t)stream);
         e = launch_attn_fwd(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_FWD], 2), (hipStream_t)stream);
     }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
+int flexsp_attn_varlen_fwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                                   flexsp_tensor v, int32_t head_begin, int32_t head_count, int32_t kv_head_begin,
+                                   int32_t kv_head_count, int causal, float scale, flexsp_tensor o, float *lse,
+                                   flexsp_stream stream)
+{
+    if (!ctx || !plan) return FLEXSP_INVALID_ARGUMENT;
+    if (plan->ctx != ctx || !plan->kvshard) return FLEXSP_PLAN_MISMATCH;
+    if (head_begin < 0 || kv_head_begin < 0 || head_count <= 0 || kv_head_count <= 0 ||
+        head_count % kv_head_count != 0)
+        return FLEXSP_INVALID_ARGUMENT;
+    if (head_count != plan->Hq || kv_head_count != plan->Hkv || (causal != 0) != (plan->causal != 0))
+        return FLEXSP_PLAN_MISMATCH;
+    if (!view_ok(q) || !view_ok(k) || !view_ok(v) || !view_ok(o) || !lse || !std::isfinite(scale))
+        return FLEXSP_INVALID_ARGUMENT;
+    if (ctx->device < 0 || !plan->dev_base) return FLEXSP_NO_DEVICE;
+    if (plan->pass[FLEXSP_PASS_FWD].items.empty()) return FLEXSP_OK;
+    {
+        hipError_t pe = plan_before_launch(plan, (hipStream_t)stream);
+        if (pe != hipSuccess) return hip_fail(pe);
+    }
+    if (scale <= 0.f) scale = 1.0f / std::sqrt((float)plan->D);
+    AttnArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.q = (const uint16_t *)q.ptr + (int64_t)head_begin * q.stride_head;
+    a.k = (const uint16_t *)k.ptr + (int64_t)kv_head_begin * k.stride_head;
+    a.v = (const uint16_t *)v.ptr + (int64_t)kv_head_begin * v.stride_head;
+    a.out_o = (uint16_t *)o.ptr + (int64_t)head_begin * o.stride_head;
+    a.q_st = (int32_t)q.stride_token; a.q_sh = (int32_t)q.stride_head;
+    a.k_st = (int32_t)k.stride_token; a.k_sh = (int32_t)k.stride_head;
+    a.v_st = (int32_t)v.stride_token; a.v_sh = (int32_t)v.stride_head;
+    a.o_st = (int32_t)o.stride_token; a.o_sh = (int32_t)o.stride_head;
+    a.lse_out = lse;
+    a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
+    a.scale = scale; a.scale_l2 = scale * 1.4426950408889634f;
+    a.pq = plan->dq[FLEXSP_PASS_FWD];
+    hipError_t e;
+    {
+        Timed tm(ctx, FLEXSP_K_FWD, (hipStream_t)stream);
+        e = launch_attn_fwd_kvshard(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_FWD], 2), (hipStream_t)stream);
+    }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
+int flexsp_lse_merge(flexsp_ctx *ctx, flexsp_tensor o_a, const float *lse_a, flexsp_tensor o_b, const float *lse_b,
+                     flexsp_tensor o_out, float *lse_out, int64_t T, int32_t H, int32_t D, flexsp_stream stream)
+{
+    if (!ctx || T < 0 || H <= 0 || D <= 0) return FLEXSP_INVALID_ARGUMENT;
+    if (D != 64 && D != 128) return FLEXSP_UNSUPPORTED;  // (a row's pieces then share one wavefront: in-place use is safe)
+    if (T == 0) return FLEXSP_OK;
+    if (!view_ok(o_a) || !view_ok(o_b) || !view_ok(o_out) || !lse_a || !lse_b || !lse_out)
+        return FLEXSP_INVALID_ARGUMENT;
+    if (T * (int64_t)H * (D / 8) >= ((int64_t)1 << 31)) return FLEXSP_UNSUPPORTED;
+    if (ctx->device < 0) return FLEXSP_NO_DEVICE;
+    hipError_t e = launch_lse_merge((const uint16_t *)o_a.ptr, lse_a, (const uint16_t *)o_b.ptr, lse_b,
+                                    (uint16_t *)o_out.ptr, lse_out, T, H, D, (int32_t)o_a.stride_token,
+                                    (int32_t)o_a.stride_head, (int32_t)o_b.stride_token, (int32_t)o_b.stride_head,
+                                    (int32_t)o_out.stride_token, (int32_t)o_out.stride_head, (hipStream_t)stream);
     return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
 }
 

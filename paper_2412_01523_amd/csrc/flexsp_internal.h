@@ -22,6 +22,13 @@ constexpr int kDkvBq = 64;     // query rows per dK/dV step
 constexpr int kThreads = 256;  // every attention kernel runs 4 wavefronts per workgroup
 constexpr int kMaxQueues = 8;  // one work queue per XCD
 
+// Work item of the key-shard forward: query rows q_start .. q_start+q_len-1 of q / o / lse, shard
+// keys k_start .. k_start+k_len-1 of k / v, shift = position of the first query in its sequence
+// minus position of the shard's first key.  `tile` counts 128-row query tiles.
+struct flexsp_shard_item {
+    int32_t q_start, q_len, k_start, k_len, shift, tile, head, pad;
+};
+
 struct PassQueues {
     const flexsp_item *items;  // device, all queues back to back
     const int32_t *offsets;    // device, nq + 1 boundaries into items
@@ -56,6 +63,10 @@ hipError_t launch_pack(const void *src, void *dst, int64_t T, int H, int D, int 
 hipError_t launch_pack_many(int n, const void *const *src, void *const *dst, int64_t T, const int32_t *H, int D,
                             int P, int eb, bool unpack, hipStream_t s);
 hipError_t launch_attn_fwd(const AttnArgs &a, int D, int grid, hipStream_t s);
+hipError_t launch_attn_fwd_kvshard(const AttnArgs &a, int D, int grid, hipStream_t s);  // a.pq.items: flexsp_shard_item
+hipError_t launch_lse_merge(const uint16_t *oa, const float *la, const uint16_t *ob, const float *lb, uint16_t *oo,
+                            float *lo, int64_t T, int H, int D, int32_t oa_st, int32_t oa_sh, int32_t ob_st,
+                            int32_t ob_sh, int32_t oo_st, int32_t oo_sh, hipStream_t s);
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s);
 

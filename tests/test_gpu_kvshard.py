@@ -1,0 +1,209 @@
+"""GPU parity of the context-parallel pieces (paper Sec. 2.1.3, paragraph "Context Parallelism", and
+the appendix on integrating it): attention of packed queries against ONE SHARD of each sequence's keys
+(flexsp_attn_varlen_fwd_kvshard) and the log-sum-exp merge of such partial results (flexsp_lse_merge),
+through the C ABI, against the CPU fp64 oracle on the same seeded inputs.  Tolerances as for the
+forward: O within max-abs 2e-2 and relative L2 5e-3, LSE within 1e-3 where finite; rows that see no
+key must come out as O = 0, LSE = -inf exactly."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2412_01523_amd import workloads as wl
+
+from gpu_util import MAX_ABS, REL_L2, bf16_f64, errors, to_bits, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2412_01523_amd import binding as fx
+    c = fx.Context(0)
+    yield c
+    c.close()
+
+
+def _shard_forward(ctx, q, k, v, cu_q, cu_k, shift, causal):
+    """HIP path: (O bits [Tq,Hq,D], LSE [Hq,Tq] fp32) as device tensors."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    Tq, Hq, D = q.shape
+    Hkv = k.shape[1]
+    plan = fx.ShardPlan(ctx, cu_q, cu_k, shift, Hq, Hkv, D, causal)
+    qd = to_dev(q)
+    kd = to_dev(k) if k.shape[0] else torch.zeros((8, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    vd = to_dev(v) if v.shape[0] else torch.zeros((8, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    o = torch.full((Tq, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((Hq, Tq), float("nan"), dtype=torch.float32, device="cuda")
+    fx.flexsp_attn_varlen_fwd_kvshard(ctx, plan, qd, kd, vd, o, lse, causal=causal)
+    torch.cuda.synchronize()
+    plan.close()
+    return o, lse
+
+
+def _compare(tag, o, lse, O, LSE):
+    got = bf16_f64(to_bits(o))
+    assert np.isfinite(got).all(), f"{tag}: non-finite O"
+    ma, rl = errors(got, O)
+    L = lse.cpu().numpy().astype(np.float64)
+    dead = np.isneginf(LSE)
+    assert (np.isneginf(L) == dead).all(), f"{tag}: rows without a visible key differ"
+    assert not got[dead.T].any(), f"{tag}: a row without keys is not zero"
+    el = float(np.abs(L[~dead] - LSE[~dead]).max(initial=0.0))
+    say(f"  {tag}: O max_abs={ma:.2e} rel_l2={rl:.2e} LSE max_abs={el:.2e} rows without keys={int(dead.sum())}")
+    assert ma <= MAX_ABS and rl <= REL_L2 and el < 1e-3, tag
+
+
+SHARD_CASES = [
+    # name, query lengths, key lengths, shift per sequence, Hq, Hkv, D, causal
+    ("aligned", [128, 64, 300], [128, 64, 300], [0, 0, 0], 2, 2, 128, True),               # = ordinary causal attention
+    ("odd-shifts", [100, 257, 33, 200], [150, 257, 90, 64], [5, -17, 70, 1], 4, 2, 128, True),
+    ("late-chunk", [300, 130], [1500, 700], [1200, 570], 2, 2, 128, True),                 # last queries, all keys: many unmasked tiles
+    ("early-keys-long", [700], [2000], [1300], 2, 1, 128, True),
+    ("nothing-visible", [130, 64, 200], [300, 100, 0], [-400, -64, 0], 2, 2, 128, True),  # keys lie after the queries / empty shard
+    ("partly-visible", [200, 129], [128, 300], [-100, -128], 2, 2, 64, True),
+    ("noncausal", [70, 300, 1], [129, 64, 500], [0, 0, 0], 4, 2, 64, False),
+    ("noncausal-d128", [513, 31], [1000, 257], [-9, 9], 2, 2, 128, False),
+    ("ragged-keys", [64, 64, 64], [1, 31, 33], [100, 100, 100], 2, 2, 128, True),
+]
+
+
+@pytest.mark.parametrize("name,lq,lk,shift,Hq,Hkv,D,causal", SHARD_CASES, ids=[c[0] for c in SHARD_CASES])
+def test_kvshard_forward_matches_oracle_elementwise(ctx, name, lq, lk, shift, Hq, Hkv, D, causal):
+    say(f"key-shard case {name}: queries {lq} keys {lk} shift {shift} Hq={Hq} Hkv={Hkv} D={D} causal={causal}")
+    seed = 5200 + len(name)
+    q = wl.normal_bf16(seed, wl.TID_Q, (sum(lq), Hq, D))
+    k = wl.normal_bf16(seed, wl.TID_K, (sum(lk), Hkv, D))
+    v = wl.normal_bf16(seed, wl.TID_V, (sum(lk), Hkv, D))
+    cu_q, cu_k = wl.cu_seqlens(lq), wl.cu_seqlens(lk)
+    O, LSE = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, shift, causal)
+    o, lse = _shard_forward(ctx, q, k, v, cu_q, cu_k, shift, causal)
+    _compare(name, o, lse, O, LSE)
+
+
+def test_aligned_shard_equals_the_ordinary_forward_bitwise(ctx):
+    """shift = 0 and keys = the whole sequence is ordinary causal attention: same kernel arithmetic,
+    so the key-shard call must reproduce flexsp_attn_varlen_fwd bit for bit."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    lens, Hq, Hkv, D = [700, 64, 129, 1], 4, 2, 128
+    cu = wl.cu_seqlens(lens)
+    q, k, v = (wl.normal_bf16(5300, t, (sum(lens), h, D)) for t, h in ((0, Hq), (1, Hkv), (2, Hkv)))
+    o, lse = _shard_forward(ctx, q, k, v, cu, cu, [0] * len(lens), True)
+    plan = fx.Plan(ctx, cu, Hq, Hkv, D, True)
+    o2 = torch.empty_like(o); lse2 = torch.empty_like(lse)
+    fx.flexsp_attn_varlen_fwd(ctx, plan, to_dev(q), to_dev(k), to_dev(v), None, o2, lse2)
+    torch.cuda.synchronize()
+    plan.close()
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16)) and torch.equal(lse, lse2)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_ring_of_three_shards_merges_into_the_full_attention(ctx, causal):
+    """One device's view of a context-parallel ring, without the wire: its query chunk of every
+    sequence meets the keys in three shards, one after the other, and folds each partial result into
+    the running one with flexsp_lse_merge (in place).  The result must be the attention over all
+    keys (oracle, and the HIP forward on the unsplit batch)."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    lens, Hq, Hkv, D = [900, 64, 1, 333, 1500], 4, 2, 128
+    cu = wl.cu_seqlens(lens)
+    T = sum(lens)
+    q = wl.normal_bf16(5400, wl.TID_Q, (T, Hq, D))
+    k = wl.normal_bf16(5400, wl.TID_K, (T, Hkv, D))
+    v = wl.normal_bf16(5400, wl.TID_V, (T, Hkv, D))
+    O, LSE = oracle.attn_fwd(q, k, v, cu, causal)
+    rng = np.random.default_rng(54)
+    a0 = [int(rng.integers(0, max(s // 2, 1))) for s in lens]          # this device's query chunk: rows a0 .. s-1
+    c1 = [int(rng.integers(0, s + 1)) for s in lens]
+    c2 = [int(rng.integers(c, s + 1)) for c, s in zip(c1, lens)]
+    say(f"ring: lens={lens} query chunks start at {a0}, key cuts {c1} {c2}, causal={causal}")
+
+    def rows(x, lo, hi):
+        return np.concatenate([x[int(cu[b]) + lo[b]: int(cu[b]) + hi[b]] for b in range(len(lens))])
+
+    qs = rows(q, a0, lens)
+    cu_q = wl.cu_seqlens([s - a for s, a in zip(lens, a0)])
+    acc_o = acc_l = None
+    for lo, hi in (([0] * len(lens), c1), (c1, c2), (c2, list(lens))):
+        cu_k = wl.cu_seqlens([h - l for l, h in zip(lo, hi)])
+        shift = [a - l for a, l in zip(a0, lo)]
+        o, lse = _shard_forward(ctx, qs, rows(k, lo, hi), rows(v, lo, hi), cu_q, cu_k, shift, causal)
+        if acc_o is None:
+            acc_o, acc_l = o, lse
+        else:
+            fx.flexsp_lse_merge(ctx, acc_o, acc_l, o, lse, acc_o, acc_l)      # fold in place
+    torch.cuda.synchronize()
+    Oq = rows(O, a0, lens)
+    Lq = np.concatenate([LSE[:, int(cu[b]) + a0[b]: int(cu[b + 1])] for b in range(len(lens))], axis=1)
+    _compare(f"ring causal={causal}", acc_o, acc_l, Oq, Lq)
+    # and against the HIP forward on the unsplit batch: the same numbers up to the extra roundings of the parts
+    plan = fx.Plan(ctx, cu, Hq, Hkv, D, causal)
+    o_full = torch.empty((T, Hq, D), dtype=torch.bfloat16, device="cuda")
+    l_full = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+    fx.flexsp_attn_varlen_fwd(ctx, plan, to_dev(q), to_dev(k), to_dev(v), None, o_full, l_full, causal=causal)
+    torch.cuda.synchronize()
+    plan.close()
+    d = bf16_f64(to_bits(acc_o)) - rows(bf16_f64(to_bits(o_full)), a0, lens)
+    assert np.abs(d).max() <= MAX_ABS
+
+
+def test_lse_merge_matches_oracle_and_ignores_parts_without_keys(ctx):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    for T, H, D in ((300, 3, 128), (129, 2, 64)):
+        rng = np.random.default_rng(T)
+        oa = wl.normal_bf16(5500, 0, (T, H, D)); ob = wl.normal_bf16(5500, 1, (T, H, D))
+        la = rng.normal(3.0, 2.0, (H, T)).astype(np.float32); lb = rng.normal(3.0, 2.0, (H, T)).astype(np.float32)
+        la[0, ::7] = -np.inf                      # part a saw no key on these rows ...
+        lb[0, ::5] = -np.inf                      # ... part b on these (every 35th row: neither did)
+        oa_f, ob_f = bf16_f64(oa), bf16_f64(ob)
+        O, L = oracle.lse_merge(oa_f, la, ob_f, lb)
+        oa_dev, ob_dev = to_dev(oa), to_dev(ob)
+        oa_dev[::7, 0] = float("nan")             # whatever a part without keys holds must not leak
+        la_d, lb_d = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+        out = torch.full((T, H, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lo = torch.full((H, T), float("nan"), dtype=torch.float32, device="cuda")
+        fx.flexsp_lse_merge(ctx, oa_dev, la_d, ob_dev, lb_d, out, lo)
+        torch.cuda.synchronize()
+        got, gl = bf16_f64(to_bits(out)), lo.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        dead = np.isneginf(L)
+        assert (np.isneginf(gl) == dead).all() and not got[dead.T].any()
+        assert np.abs(gl[~dead] - L[~dead]).max() < 1e-5 * (1 + np.abs(L[~dead]).max())
+        # one rounding of the result to bf16 plus fp32 arithmetic
+        assert (np.abs(got - O) <= 2.0 ** -8 * np.abs(O) + 1e-5).all()
+        # strided views (heads 1.. of a wider tensor) and in-place use give the same bits
+        wide = torch.zeros((T, H + 2, D), dtype=torch.bfloat16, device="cuda")
+        wide[:, 1:H + 1] = oa_dev
+        fx.flexsp_lse_merge(ctx, wide[:, 1:H + 1], la_d, ob_dev, lb_d, wide[:, 1:H + 1], la_d)
+        torch.cuda.synchronize()
+        assert torch.equal(wide[:, 1:H + 1].contiguous().view(torch.int16), out.view(torch.int16))
+        assert torch.equal(la_d, lo) and not wide[:, 0].any() and not wide[:, H + 1].any()
+
+
+def test_kvshard_error_paths(ctx):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    cu = wl.cu_seqlens([64])
+    t = torch.zeros((64, 2, 64), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((2, 64), dtype=torch.float32, device="cuda")
+    shard = fx.ShardPlan(ctx, cu, cu, [0], 2, 2, 64, True)
+    plain = fx.Plan(ctx, cu, 2, 2, 64, True)
+    with pytest.raises(fx.FlexspError) as e:
+        fx.flexsp_attn_varlen_fwd(ctx, shard, t, t, t, None, t, lse)                 # a key-shard plan serves its own call only
+    assert e.value.status == fx.PLAN_MISMATCH
+    with pytest.raises(fx.FlexspError) as e:
+        fx.flexsp_attn_varlen_fwd_kvshard(ctx, plain, t, t, t, t, lse)
+    assert e.value.status == fx.PLAN_MISMATCH
+    with pytest.raises(fx.FlexspError) as e:
+        fx.flexsp_attn_varlen_bwd(ctx, shard, t, t, t, t, t, lse, None, t, t, t)
+    assert e.value.status == fx.PLAN_MISMATCH
+    shard.close(); plain.close()

@@ -189,3 +189,37 @@ def test_permute_and_attention_validation_without_a_device(host_ctx):
     assert f(h, plan.handle, t, t, t, a, 0, 2, 0, 2, 1, 0.0, t, None, None) == fx.INVALID_ARGUMENT      # lse is required
     assert f(h, None, t, t, t, a, 0, 2, 0, 2, 1, 0.0, t, lse, None) == fx.INVALID_ARGUMENT
     plan.close()
+
+
+def test_kvshard_plan_lists_every_query_tile_and_validates(host_ctx):
+    """Host logic of flexsp_plan_create_kvshard: one item per (sequence with queries, 128-row query
+    tile, head), whatever the shard holds; an item names its sequence by index; queues are ordered by
+    the key tiles an item can see, most first; bad prefix sums and offsets are refused."""
+    import ctypes
+    lq, lk, shift = [300, 0, 64, 129], [1000, 50, 0, 129], [700, 0, 0, -64]
+    cu_q, cu_k = wl.cu_seqlens(lq), wl.cu_seqlens(lk)
+    plan = fx.ShardPlan(host_ctx, cu_q, cu_k, shift, 2, 1, 128, True)
+    items, offs = plan.items(fx.PASS_FWD)
+    want = sorted((b, t, h) for b, s in enumerate(lq) for t in range((s + 127) // 128) for h in range(2))
+    assert sorted(zip(items["seq_start"].tolist(), items["tile"].tolist(), items["head"].tolist())) == want
+    assert all(lq[b] == n for b, n in zip(items["seq_start"], items["seq_len"]))
+    assert plan.num_items(fx.PASS_BWD_DKV) == 0 and plan.num_items(fx.PASS_BWD_DQ) == 0
+
+    def visible_tiles(b, t):
+        keys = max(0, min(lk[b], (t + 1) * 128 + shift[b]))
+        return (keys + 63) // 64
+    for x in range(len(offs) - 1):
+        cost = [visible_tiles(int(items["seq_start"][i]), int(items["tile"][i])) for i in range(int(offs[x]), int(offs[x + 1]))]
+        assert cost == sorted(cost, reverse=True)
+    plan.close()
+    L = fx.lib()
+    h = ctypes.c_void_p()
+    i32 = lambda xs: np.array(xs, dtype=np.int32).ctypes.data_as(ctypes.c_void_p)
+    mk = lambda q, k, sh, B=1, D=128: L.flexsp_plan_create_kvshard(host_ctx.handle, i32(q), i32(k), i32(sh), B, 2, 2, D, 1,
+                                                                    ctypes.byref(h))
+    assert mk([0, 64], [0, 64], [0]) == fx.OK
+    L.flexsp_plan_destroy(h)
+    assert mk([1, 64], [0, 64], [0]) == fx.INVALID_ARGUMENT          # cu_q[0] != 0
+    assert mk([0, 64], [0, -1], [0]) == fx.INVALID_ARGUMENT          # decreasing key prefix sums
+    assert mk([0, 64], [0, 64], [2 ** 31 - 1]) == fx.INVALID_ARGUMENT
+    assert mk([0, 64], [0, 64], [0], D=96) == fx.UNSUPPORTED

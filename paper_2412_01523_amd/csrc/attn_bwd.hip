@@ -56,6 +56,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
     const int kb = wave >> 1, j = wave & 1;     // key block; role: 0 accumulates dV, 1 accumulates dK
     LaneOffsets<D> lo;
     lo.init(lane0);
+    // What depends on the wavefront's role is folded into the per-lane offsets once: phase 1 reads the
+    // rows of query block j, phase 2 reads the dO tile (role 0) or the Q tile (role 1).  Every LDS
+    // read of a step is then "offset register + compile-time constant", with no address arithmetic.
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) lo.nat[ks] += j * 32 * L::ROWB;
+#pragma unroll
+    for (int db = 0; db < DB; db++) {
+        lo.tr[db][0] += j ? 0 : QTILE;
+        lo.tr[db][1] += j ? 0 : QTILE;
+    }
     __shared__ int deal_word;
     ItemDealer deal;
 
@@ -123,7 +133,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             constexpr int BUF = decltype(bufc)::value;
             const char *sQ = smem + BUF * STEP;
             const char *sG = sQ + QTILE;
-            const float *sL = (const float *)(sQ + 2 * QTILE);  // lse2[64], delta[64]
+            const float *sL = (const float *)(sQ + 2 * QTILE);  // lse2[64], -delta[64]
             const int q_lo = qfirst + (step % nsteps) * BQ;
             // a block (32 queries x the pair's 32 keys) is empty when it lies past the end of the
             // sequence or wholly above the diagonal; both wavefronts of a pair agree on that
@@ -143,14 +153,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             uint32_t pp[8], dd[8];
             const int my_lo = q_lo + j * 32;
             if (!empty(j)) {
+                // The dP accumulator starts at -delta of its rows (the scratch holds delta negated), so the
+                // matrix instructions deliver dP - delta and the subtraction costs no vector instruction.
                 f32x16 sacc, pacc;
 #pragma unroll
-                for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
+                for (int i4 = 0; i4 < 4; i4++) {
+                    const f32x4 d4 = *(const f32x4 *)(sL + 64 + j * 32 + 8 * i4 + 4 * hl);
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        sacc[4 * i4 + e] = 0.f;
+                        pacc[4 * i4 + e] = d4[e];
+                    }
+                }
                 {
                     // fragment n: k step n / 2 of the Q tile (n even) or the dO tile (n odd); read AH ahead
                     constexpr int AH = kReadAhead, N = 2 * KS;
                     bf16x8 fr[N];
-                    auto rd = [&](int n) { return lds_nat((n & 1) ? sG : sQ, j * 32 * L::ROWB + lo.nat[n >> 1]); };
+                    auto rd = [&](int n) { return lds_nat((n & 1) ? sG : sQ, lo.nat[n >> 1]); };  // (rows of block j: see lo.nat above)
 #pragma unroll
                     for (int n = 0; n < AH; n++) fr[n] = rd(n);
 #pragma unroll
@@ -170,7 +189,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
 #pragma unroll
                     for (int i4 = 0; i4 < 4; i4++) {
                         const f32x4 l4 = *(const f32x4 *)(sL + j * 32 + 8 * i4 + 4 * hl);
-                        const f32x4 d4 = *(const f32x4 *)(sL + 64 + j * 32 + 8 * i4 + 4 * hl);
                         float p[4], ds[4];
 #pragma unroll
                         for (int e = 0; e < 4; e++) {
@@ -179,7 +197,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                                 const int qr = my_lo + 8 * i4 + 4 * hl + e;
                                 p[e] = ((a.causal && qr < kvrow) || qr >= s) ? 0.f : p[e];
                             }
-                            ds[e] = p[e] * (pacc[4 * i4 + e] - d4[e]);
+                            ds[e] = p[e] * pacc[4 * i4 + e];
                         }
                         pp[2 * i4] = pack_bf16x2(p[0], p[1]);
                         pp[2 * i4 + 1] = pack_bf16x2(p[2], p[3]);
@@ -200,7 +218,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             __syncthreads();  // the partner's fragments are visible
 
             // ---- phase 2: role 0: dV^T += dO^T P, role 1: dK^T += Q^T dS, both query blocks
-            const char *sX = j ? sQ : sG;
+            const char *sX = sQ;  // (+ QTILE for role 0, inside lo.tr)
 #pragma unroll
             for (int qb = 0; qb < 2; qb++) {
                 if (empty(qb)) continue;
@@ -429,7 +447,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         // (stored here, not where they are computed: a store in flight there would be waited for by
         // the first tile's wait for its copy)
         if (qok && hl == 0) {
-            a.delta_out[(int64_t)h * a.T + tok0 + qrow] = delta;
+            a.delta_out[(int64_t)h * a.T + tok0 + qrow] = -delta;  // negated: the dK/dV kernel starts its dP accumulator from it
             a.lse_out[(int64_t)h * a.T + tok0 + qrow] = lse2;
         }
         if (a.grad_f32) {

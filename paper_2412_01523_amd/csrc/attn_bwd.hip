@@ -150,6 +150,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             // sequences; the same move in the dQ kernel cost 2 %)
 
             // ---- phase 1: P and dS of query block j
+            // (matrix phases run at raised wave priority, the arithmetic between them at the base one: when
+            // both workgroups of a compute unit want the matrix pipe, the one already in a matrix phase
+            // finishes it first instead of both crawling through it together; 2-3 % on this kernel)
+            __builtin_amdgcn_s_setprio(2);
             uint32_t pp[8], dd[8];
             const int my_lo = q_lo + j * 32;
             if (!empty(j)) {
@@ -181,6 +185,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                             sacc = mfma32(fr[n], kf[n >> 1], sacc);
                     }
                 }
+                __builtin_amdgcn_s_setprio(0);
                 if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
                 // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e
                 const bool masked = (a.causal && my_lo < wk_lo + 31) || (my_lo + 32 > s);
@@ -216,6 +221,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             }
             if (empty(j) && step + 1 < total) prefetch(step + 1, BUF ^ 1);  // no phase 1: the copies go out here
             __syncthreads();  // the partner's fragments are visible
+            __builtin_amdgcn_s_setprio(2);
 
             // ---- phase 2: role 0: dV^T += dO^T P, role 1: dK^T += Q^T dS, both query blocks
             const char *sX = sQ;  // (+ QTILE for role 0, inside lo.tr)
@@ -247,6 +253,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                     }
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
         };
         for (int step = 0; step < total; step += 2) {
             step_fn(std::integral_constant<int, 0>{}, step);

@@ -106,12 +106,26 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu_seqlens_host, int32_t 
                        int32_t Hq, int32_t Hkv, int32_t D, int causal, flexsp_plan **out);
 void flexsp_plan_destroy(flexsp_plan *plan);
 
-/* Plan inspection (host logic; works for host-only contexts). */
+/* Plan inspection (host logic; works for host-only contexts).
+ * A work item is one tile of one (sequence, head): 128 query rows (forward, dQ pass) walking the key
+ * tiles they can see, or 64 keys (dK/dV pass) walking the query rows that see them, for every query
+ * head of the kv head's group.  When a batch has so few, so long items that the longest would outlast
+ * an even share of the whole pass (few heads, a dominant sequence: the usual case for a large
+ * sequence-parallel group), the plan cuts such a tile's inner loop into `nparts` consecutive ranges,
+ * one work item each; every part leaves its partial result (fp32) in the plan's scratch and the part
+ * that finishes last adds them up in part order and writes the tile, so results do not depend on
+ * which part that is. */
 typedef struct flexsp_item {
     int32_t seq_start; /* first token of the sequence in the packed stream            */
     int32_t seq_len;   /* its length                                                   */
     int32_t tile;      /* tile index inside the sequence (query tile or key tile)      */
     int32_t head;      /* query head (forward, dQ pass) or kv head (dK/dV pass)        */
+    int32_t step_begin; /* the item walks steps step_begin .. step_end-1 of the tile's inner loop    */
+    int32_t step_end;   /* (a step = 64 keys for a query tile; 64 query rows of one head of the group
+                           for a key tile, heads one after the other); a whole tile: 0 .. its step count */
+    int32_t slot;       /* nparts > 1: first partial-result record of the tile; else -1              */
+    int32_t parts;      /* (part << 16) | nparts: this item is part `part` of `nparts` of its tile
+                           (0 and 1 for a whole tile)                                                */
 } flexsp_item;
 enum { FLEXSP_PASS_FWD = 0, FLEXSP_PASS_BWD_DKV = 1, FLEXSP_PASS_BWD_DQ = 2 };
 /* Number of items of a pass, or a negative status. */
@@ -264,7 +278,7 @@ int flexsp_lse_merge(flexsp_ctx *ctx, flexsp_tensor o_a, const float *lse_a, fle
  * no plan and calls no hipMalloc, hipFree or any other allocating routine: the work queues are built
  * on the device from `cu_seqlens_dev` (device pointer, B+1 int32 prefix sums, cu[0] = 0,
  * non-decreasing, cu[B] <= T) by a small kernel launched in front of the attention kernel, into a
- * fixed array of about 1 MiB that each GPU the library runs on holds from library load until the
+ * fixed array of about 2 MiB that each GPU the library runs on holds from library load until the
  * process ends (its address on the context's device is resolved by flexsp_ctx_create).
  *   B, T            sequences in the batch; tokens the q / k / v / o tensors hold (rows of lse)
  *   D               head dim, 64 or 128; the remaining arguments are those of flexsp_attn_varlen_fwd

@@ -47,7 +47,8 @@ class Tensor(Structure):
 
 
 class Item(Structure):
-    _fields_ = [("seq_start", c_int32), ("seq_len", c_int32), ("tile", c_int32), ("head", c_int32)]
+    _fields_ = [("seq_start", c_int32), ("seq_len", c_int32), ("tile", c_int32), ("head", c_int32),
+                ("step_begin", c_int32), ("step_end", c_int32), ("slot", c_int32), ("parts", c_int32)]
 
 
 class Profile(Structure):
@@ -200,12 +201,17 @@ class Plan:
     def items(self, which: int):
         """(items as a structured numpy array, queue offsets)"""
         n = self.num_items(which)
-        arr = np.zeros(n, dtype=np.dtype([("seq_start", "<i4"), ("seq_len", "<i4"), ("tile", "<i4"),
-                                          ("head", "<i4")]))
+        arr = np.zeros(n, dtype=np.dtype([("seq_start", "<i4"), ("seq_len", "<i4"), ("tile", "<i4"), ("head", "<i4"),
+                                          ("step_begin", "<i4"), ("step_end", "<i4"), ("slot", "<i4"), ("parts", "<i4")]))
         offs = np.zeros(self.ctx.num_xcd + 1, dtype=np.int64)
         _check(lib().flexsp_plan_get_items(self.handle, which, arr.ctypes.data_as(c_void_p), n,
                                            offs.ctypes.data_as(c_void_p)), "flexsp_plan_get_items")
-        return arr, offs
+        # the packed `parts` field, unpacked for convenience
+        out = np.zeros(n, dtype=np.dtype(arr.dtype.descr + [("part", "<i4"), ("nparts", "<i4")]))
+        for name in arr.dtype.names:
+            out[name] = arr[name]
+        out["part"], out["nparts"] = arr["parts"] >> 16, arr["parts"] & 0xffff
+        return out, offs
 
     def tile_rows(self, which: int) -> int:
         return lib().flexsp_plan_tile_rows(self.handle, which)

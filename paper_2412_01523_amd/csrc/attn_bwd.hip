@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
         lo.tr[db][0] += j ? 0 : QTILE;
         lo.tr[db][1] += j ? 0 : QTILE;
     }
-    __shared__ int deal_word;
+    __shared__ int deal_word, split_word;
     ItemDealer deal;
 
     for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
@@ -85,16 +85,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
 
         const int qfirst = a.causal ? kv0 : 0;  // kv0 is a multiple of BQ
         const int nsteps = (s - qfirst + BQ - 1) / BQ;
-        const int total = nsteps * a.G;
+        // the item walks steps `first` .. `total`-1 of the tile's nsteps * G (all of them unless the tile was cut)
+        const int first = it.step_begin, total = it.step_end;
+        const int nparts = it.parts & 0xffff, part = it.parts >> 16;
 
         const uint32_t goffq = tile_goff<D>(a.q_st, wave, lane), goffg = tile_goff<D>(a.do_st, wave, lane);
-        auto prefetch = [&](int step, int buf) {
-            const int h = g * a.G + step / nsteps;
-            const int qs = qfirst + (step % nsteps) * BQ;
+        // Steps are counted from the item's first one (n of them); which head and which query rows a step
+        // covers is carried along instead of being divided out of a step number: (h_cur, q_cur) for the
+        // step being computed, (h_nxt, q_nxt) for the one whose tiles are fetched meanwhile.
+        const int n = total - first;
+        const int q_end = qfirst + nsteps * BQ;
+        int h_cur = g * a.G + first / nsteps, q_cur = qfirst + (first % nsteps) * BQ;
+        int h_nxt = h_cur, q_nxt = q_cur;
+        auto advance_nxt = [&]() {
+            q_nxt += BQ;
+            if (q_nxt >= q_end) {
+                q_nxt = qfirst;
+                h_nxt++;
+            }
+        };
+        auto prefetch = [&](int h, int qs, int buf) {
             char *base = smem + buf * STEP;
             const uint16_t *qb = a.q + tok0 * a.q_st + (int64_t)h * a.q_sh;
             const uint16_t *gb = a.dO + tok0 * a.do_st + (int64_t)h * a.do_sh;
-            if (qs + BQ <= s) {  // whole tile inside the sequence
+            if (__builtin_expect(qs + BQ <= s, 1)) {  // whole tile inside the sequence
                 load_tile_async_fast<D, BQ>(base, qb + (int64_t)qs * a.q_st, a.q_st, goffq, wave);
                 load_tile_async_fast<D, BQ>(base + QTILE, gb + (int64_t)qs * a.do_st, a.do_st, goffg, wave);
             } else {
@@ -106,7 +120,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 global_to_lds4(src, base + 2 * QTILE + wave * 256);
             }
         };
-        if (total > 0) prefetch(0, 0);
+        if (n > 0) prefetch(h_cur, q_cur, 0);
+        advance_nxt();
 
         // K and V fragments of the pair's 32 keys (B operands: column = key, k = head dim)
         bf16x8 kf[KS], vf[KS];
@@ -134,7 +149,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             const char *sQ = smem + BUF * STEP;
             const char *sG = sQ + QTILE;
             const float *sL = (const float *)(sQ + 2 * QTILE);  // lse2[64], -delta[64]
-            const int q_lo = qfirst + (step % nsteps) * BQ;
+            const int q_lo = q_cur;
             // a block (32 queries x the pair's 32 keys) is empty when it lies past the end of the
             // sequence or wholly above the diagonal; both wavefronts of a pair agree on that
             auto empty = [&](int qb) {
@@ -186,7 +201,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                     }
                 }
                 __builtin_amdgcn_s_setprio(0);
-                if (step + 1 < total) prefetch(step + 1, BUF ^ 1);
+                if (__builtin_expect(step + 1 < n, 1)) prefetch(h_nxt, q_nxt, BUF ^ 1);
                 // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e
                 const bool masked = (a.causal && my_lo < wk_lo + 31) || (my_lo + 32 > s);
                 auto probs = [&](auto maskc) {
@@ -219,7 +234,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 *(u32x4 *)(slot) = j ? u32x4{pp[0], pp[1], pp[2], pp[3]} : u32x4{dd[0], dd[1], dd[2], dd[3]};
                 *(u32x4 *)(slot + 1024) = j ? u32x4{pp[4], pp[5], pp[6], pp[7]} : u32x4{dd[4], dd[5], dd[6], dd[7]};
             }
-            if (empty(j) && step + 1 < total) prefetch(step + 1, BUF ^ 1);  // no phase 1: the copies go out here
+            if (empty(j) && step + 1 < n) prefetch(h_nxt, q_nxt, BUF ^ 1);  // no phase 1: the copies go out here
             __syncthreads();  // the partner's fragments are visible
             __builtin_amdgcn_s_setprio(2);
 
@@ -254,10 +269,23 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 }
             }
             __builtin_amdgcn_s_setprio(0);
+            h_cur = h_nxt;
+            q_cur = q_nxt;
+            advance_nxt();
         };
-        for (int step = 0; step < total; step += 2) {
+        for (int step = 0; step < n; step += 2) {
             step_fn(std::integral_constant<int, 0>{}, step);
-            if (step + 1 < total) step_fn(std::integral_constant<int, 1>{}, step + 1);
+            if (step + 1 < n) step_fn(std::integral_constant<int, 1>{}, step + 1);
+        }
+        if (nparts > 1) {
+            split_store<DB>(a.pq.split_scratch + (int64_t)(it.slot + part) * kPartialBytes, accT, tid);
+            if (!split_arrive(a.pq.split_flags + it.slot, nparts, &split_word, tid)) continue;  // a later part finishes the tile
+#pragma unroll
+            for (int d = 0; d < DB; d++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) accT[d][i] = 0.f;
+            for (int p = 0; p < nparts; p++)
+                split_sum<DB>(a.pq.split_scratch + (int64_t)(it.slot + p) * kPartialBytes, accT, 1.0f, tid);
         }
 
         // role 0 writes dV rows, role 1 writes dK rows (scaled)
@@ -268,7 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             if (kvrow < s) store_rowT<DB>(out + ((tok0 + kvrow) * ost + (int64_t)g * osh) * 4, true, accT, mul, hl);
         } else if (wk_lo < s) {
             // through the Q/dO buffer the last step did not use (every wavefront is past its barriers)
-            store_rowT_bf16_lds<DB>(smem + (total & 1) * STEP + wave * (32 * L::ROWB),
+            store_rowT_bf16_lds<DB>(smem + (n & 1) * STEP + wave * (32 * L::ROWB),
                                     (uint16_t *)out + (tok0 + wk_lo) * ost + (int64_t)g * osh, ost,
                                     min(32, s - wk_lo), accT, mul, lane);
         }
@@ -292,7 +320,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     LaneOffsets<D> lo;
     lo.init(lane0);
-    __shared__ int deal_word;
+    __shared__ int deal_word, split_word;
     ItemDealer deal;
 
     for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
@@ -306,25 +334,29 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         const int s = it.seq_len, h = it.head, g = h / a.G;
         const int q0 = it.tile * kDqBq;
         const int64_t tok0 = it.seq_start;
-        const int kv_end = a.causal ? min(s, q0 + kDqBq) : s;
-        const int ntiles = (kv_end + kDqBk - 1) / kDqBk;
-        const uint16_t *kbase = a.k + tok0 * a.k_st + (int64_t)g * a.k_sh;
-        const uint16_t *vbase = a.v + tok0 * a.v_st + (int64_t)g * a.v_sh;
+        // The item walks key tiles step_begin .. step_end-1 (all of them unless the tile was cut: then it
+        // hands its partial dQ over).  From here on keys are counted from the item's first one: koff keys
+        // are skipped, `sk` remain, and a row's own position among them is its row index minus koff.
+        const int koff = it.step_begin * kDqBk, ntiles = it.step_end - it.step_begin, sk = s - koff;
+        const int nparts = it.parts & 0xffff, part = it.parts >> 16;
+        const uint16_t *kbase = a.k + (tok0 + koff) * a.k_st + (int64_t)g * a.k_sh;
+        const uint16_t *vbase = a.v + (tok0 + koff) * a.v_st + (int64_t)g * a.v_sh;
         const uint32_t goffk = tile_goff<D>(a.k_st, wave, lane), goffv = tile_goff<D>(a.v_st, wave, lane);
         auto prefetch = [&](int t, int buf) {
             char *dk = smem + buf * 2 * TILE, *dv = dk + TILE;
-            if ((t + 1) * kDqBk <= s) {  // whole tile inside the sequence
+            if (__builtin_expect((t + 1) * kDqBk <= sk, 1)) {  // whole tile inside the sequence
                 load_tile_async_fast<D, kDqBk>(dk, kbase + (int64_t)t * kDqBk * a.k_st, a.k_st, goffk, wave);
                 load_tile_async_fast<D, kDqBk>(dv, vbase + (int64_t)t * kDqBk * a.v_st, a.v_st, goffv, wave);
             } else {
-                load_tile_async<D, kDqBk>(dk, kbase, a.k_st, t * kDqBk, s - 1, wave, lane);
-                load_tile_async<D, kDqBk>(dv, vbase, a.v_st, t * kDqBk, s - 1, wave, lane);
+                load_tile_async<D, kDqBk>(dk, kbase, a.k_st, t * kDqBk, sk - 1, wave, lane);
+                load_tile_async<D, kDqBk>(dv, vbase, a.v_st, t * kDqBk, sk - 1, wave, lane);
             }
         };
         prefetch(0, 0);
 
         const int qrow = q0 + wave * 32 + r;
         const int wq_lo = q0 + wave * 32;
+        const int wq_rel = wq_lo - koff;  // the wavefront's first row, counted like the keys
         const bool qok = qrow < s;
         bf16x8 qf[KS], gf[KS];  // B operands: column = query row, k = head dim
         // delta = dO . O of the row (the backward's preprocessing step, done here because this kernel
@@ -378,15 +410,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
             lo.pin();
             wait_vmem();
             __syncthreads();
-            if (t + 1 < ntiles) prefetch(t + 1, BUF ^ 1);
-            if (a.causal && kv0 > wq_lo + 31) return;
+            if (__builtin_expect(t + 1 < ntiles, 1)) prefetch(t + 1, BUF ^ 1);
+            if (a.causal && kv0 > wq_rel + 31) return;
 
-            const bool need_mask = a.causal ? (kv0 + kDqBk - 1 > wq_lo) : (kv0 + kDqBk > s);
-            const int lim = a.causal ? qrow : s - 1;
+            const bool need_mask = a.causal ? (kv0 + kDqBk - 1 > wq_rel) : (kv0 + kDqBk > sk);
+            const int lim = a.causal ? qrow - koff : sk - 1;
             // one 32-key block at a time (keeps the register count under half the file)
 #pragma unroll
             for (int kb = 0; kb < 2; kb++) {
-                if (a.causal && kv0 + kb * 32 > wq_lo + 31) continue;  // block wholly above the diagonal
+                if (a.causal && kv0 + kb * 32 > wq_rel + 31) continue;  // block wholly above the diagonal
                 f32x16 sacc, pacc;
 #pragma unroll
                 for (int i = 0; i < 16; i++) sacc[i] = pacc[i] = 0.f;
@@ -456,6 +488,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         if (qok && hl == 0) {
             a.delta_out[(int64_t)h * a.T + tok0 + qrow] = -delta;  // negated: the dK/dV kernel starts its dP accumulator from it
             a.lse_out[(int64_t)h * a.T + tok0 + qrow] = lse2;
+        }
+        if (nparts > 1) {
+            split_store<DB>(a.pq.split_scratch + (int64_t)(it.slot + part) * kPartialBytes, dqT, tid);
+            if (!split_arrive(a.pq.split_flags + it.slot, nparts, &split_word, tid)) continue;  // a later part finishes the tile
+#pragma unroll
+            for (int db = 0; db < DB; db++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) dqT[db][i] = 0.f;
+            for (int p = 0; p < nparts; p++)
+                split_sum<DB>(a.pq.split_scratch + (int64_t)(it.slot + p) * kPartialBytes, dqT, 1.0f, tid);
         }
         if (a.grad_f32) {
             if (qok)

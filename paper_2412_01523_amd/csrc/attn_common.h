@@ -336,7 +336,74 @@ __device__ __forceinline__ flexsp_item load_item(const flexsp_item *items, int i
     it.seq_len = __builtin_amdgcn_readfirstlane(v.seq_len);
     it.tile = __builtin_amdgcn_readfirstlane(v.tile);
     it.head = __builtin_amdgcn_readfirstlane(v.head);
+    it.step_begin = __builtin_amdgcn_readfirstlane(v.step_begin);
+    it.step_end = __builtin_amdgcn_readfirstlane(v.step_end);
+    it.slot = __builtin_amdgcn_readfirstlane(v.slot);
+    it.parts = __builtin_amdgcn_readfirstlane(v.parts);
     return it;
+}
+
+// ------------------------------------------------------------------------------------------
+// Split tiles.  A tile whose inner loop was cut into parts (flexsp_item::parts names more than one) is finished
+// by whichever part arrives last; nobody waits for anybody.  Every part
+//   1. stores its accumulators to its own record of the plan's scratch (split_store),
+//   2. waits until those stores have completed and counts itself in (split_arrive),
+// and the part that finds all others counted already re-reads ALL records in part order, its own
+// included (split_sum), so the sum is formed in one fixed order whichever part does it: results
+// stay bitwise reproducible.  It also clears the counter for the next launch.
+// The parts of a tile may run on different XCDs, whose L2 caches do not see each other's dirty
+// lines.  A device-wide fence would write back and invalidate a whole L2 (and with it the K/V tiles
+// every other workgroup of that XCD is streaming through it; measured: a batch with many cut tiles
+// ran 30 % slower than with no cutting at all).  So the records are written and read with
+// device-scope relaxed atomic accesses instead, which go through to memory and come from memory
+// on their own and leave the caches alone; a record store is complete when its counter reaches zero.
+// Record layout: value i of thread t at float index i * kThreads + t; the forward appends 2 floats
+// per thread (row maximum, row sum) from index 64 * kThreads on.
+__device__ __forceinline__ void split_put(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float split_get(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <int NB>
+__device__ __forceinline__ void split_store(char *rec, const f32x16 (&acc)[NB], int tid)
+{
+    float *r = (float *)rec + tid;
+#pragma unroll
+    for (int b = 0; b < NB; b++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) split_put(r + (b * 16 + i) * kThreads, acc[b][i]);
+}
+template <int NB>
+__device__ __forceinline__ void split_sum(const char *rec, f32x16 (&acc)[NB], float mul, int tid)
+{
+    const float *r = (const float *)rec + tid;
+    // every load of the record in flight, then the additions (these files are compiled in source
+    // order: a load followed by its use would wait out one trip to memory per value)
+    float v[NB * 16];
+#pragma unroll
+    for (int i = 0; i < NB * 16; i++) v[i] = split_get(r + i * kThreads);
+#pragma unroll
+    for (int b = 0; b < NB; b++)
+#pragma unroll
+        for (int i = 0; i < 16; i++) acc[b][i] += mul * v[b * 16 + i];
+}
+// Returns true in every thread of the workgroup iff this part is the last of its tile to arrive.
+// Contains two workgroup barriers; `word` is an LDS word of the caller's.
+__device__ __forceinline__ bool split_arrive(int32_t *flag, int nparts, int *word, int tid)
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's record stores have completed
+    __syncthreads();                     // ... and everybody's
+    if (tid == 0) {
+        const int seen = __hip_atomic_fetch_add(flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen == nparts - 1)  // everybody has arrived: ready for the next launch
+            __hip_atomic_store(flag, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *word = seen;
+    }
+    __syncthreads();
+    return *(volatile int *)word == nparts - 1;  // the records are read after this, by the same kind of access
 }
 
 __device__ __forceinline__ flexsp_shard_item load_shard_item(const flexsp_shard_item *items, int idx)

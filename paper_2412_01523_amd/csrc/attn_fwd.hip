@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     LaneOffsets<D> lo;
     lo.init(lane0);
-    __shared__ int deal_word;
+    __shared__ int deal_word, split_word;
     ItemDealer deal;
 
     int item = deal.first(a.pq, &deal_word, wave, lane0);
@@ -63,6 +63,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         // s: query rows of the sequence; sk: its keys; tok0 / ktok0: their first rows in q / k, v
         int s, sk, shift, h, q0;
         int64_t tok0, ktok0;
+        int part = 0, nparts = 1, slot = -1, t_lo = 0, t_hi = 0;  // (see flexsp_item): the item walks key tiles t_lo .. t_hi-1
         if constexpr (SHARD) {
             const flexsp_shard_item it = load_shard_item((const flexsp_shard_item *)a.pq.items, item);
             s = it.q_len; sk = it.k_len; shift = it.shift; h = it.head; q0 = it.tile * kFwdBq;
@@ -71,6 +72,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             const flexsp_item it = load_item(a.pq.items, item);
             s = it.seq_len; sk = s; shift = 0; h = it.head; q0 = it.tile * kFwdBq;
             tok0 = it.seq_start; ktok0 = tok0;
+            part = it.parts >> 16; nparts = it.parts & 0xffff; slot = it.slot;
+            t_lo = it.step_begin; t_hi = it.step_end;
         }
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
@@ -79,8 +82,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         const int r = lane & 31, hl = lane >> 5;
         const int g = h / a.G;
         // keys this item needs
-        const int kv_end = SHARD ? (a.causal ? max(0, min(sk, q0 + kFwdBq + shift)) : sk)
-                                 : (a.causal ? min(s, q0 + kFwdBq) : s);
+        int kv_end = SHARD ? (a.causal ? max(0, min(sk, q0 + kFwdBq + shift)) : sk)
+                           : (a.causal ? min(s, q0 + kFwdBq) : s);
+        // The item walks key tiles t_lo .. t_hi-1 (all of them unless the tile was cut).  From here on keys are counted
+        // from the part's first one (koff keys are skipped: a multiple of the tile size, so blocks
+        // stay aligned and still at most one block per wavefront needs masking); a wavefront whose
+        // rows see none of the part's keys (the part after the diagonal of the tile's upper rows) ends
+        // with maximum -inf and sum 0, which the merge below weighs with zero.
+        int koff = 0;
+        if constexpr (!SHARD) {
+            koff = t_lo * kFwdBk;
+            kv_end = min(kv_end, t_hi * kFwdBk) - koff;
+            sk = s - koff;
+            ktok0 += koff;
+        }
         if constexpr (SHARD) {
             if (kv_end <= 0) {
                 // no row of this item sees a key of the shard: O = 0, LSE = -inf (the neutral element
@@ -139,9 +154,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             cmask = a.causal ? min((wq_lo + shift) >> 5, (sk - 1) >> 5) : ((sk - 1) >> 5);  // FIRST block that needs masking
             lim = a.causal ? min(qrow + shift, sk - 1) : sk - 1;
         } else {
-            cmax = wq_lo >= s ? -1 : (a.causal ? min((kv_end - 1) >> 5, wq_lo >> 5) : (kv_end - 1) >> 5);
-            cmask = a.causal ? (wq_lo >> 5) : ((s - 1) >> 5);  // the block that needs masking
-            lim = a.causal ? qrow : s - 1;                      // largest visible key of this lane's row
+            // (wq_lo - koff is negative for rows that lie before the part's keys: >> rounds down, no block)
+            cmax = wq_lo >= s ? -1 : (a.causal ? min((kv_end - 1) >> 5, (wq_lo - koff) >> 5) : (kv_end - 1) >> 5);
+            cmask = a.causal ? ((wq_lo - koff) >> 5) : ((sk - 1) >> 5);  // the block that needs masking
+            lim = a.causal ? qrow - koff : sk - 1;                        // largest visible key of this lane's row
         }
 
         f32x16 oacc[DB];
@@ -373,7 +389,45 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         for (; t < ntiles; t++) window(t);
 
         // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
-        const float l_tot = halves_sum(l_run);
+        float l_tot = halves_sum(l_run);
+        if constexpr (!SHARD) {
+            if (nparts > 1) {
+                // hand over (O unnormalised, row maximum, row sum); the part that arrives last merges
+                // all parts in part order: O = sum_p 2^((m_p - M) scale_l2) O_p, likewise the row sums
+                const int tid_ = wave * 64 + lane;  // (recomputed: keeping threadIdx alive through the tile loop costs a register)
+                char *rec = a.pq.split_scratch + (int64_t)(slot + part) * kPartialBytes;
+                split_store<DB>(rec, oacc, tid_);
+                split_put((float *)(rec + 64 * kThreads * 4) + 2 * tid_, m_run);
+                split_put((float *)(rec + 64 * kThreads * 4) + 2 * tid_ + 1, l_tot);
+                if (!split_arrive(a.pq.split_flags + slot, nparts, &split_word, tid_)) continue;
+                // all parts' row statistics first (one trip to memory for the lot), then the records in turn
+                float mp[kMaxParts], lp[kMaxParts];
+#pragma unroll
+                for (int p = 0; p < kMaxParts; p++) {
+                    const float *st = (const float *)(a.pq.split_scratch + (int64_t)(slot + min(p, nparts - 1)) * kPartialBytes +
+                                                      64 * kThreads * 4) + 2 * tid_;
+                    mp[p] = split_get(st);
+                    lp[p] = split_get(st + 1);
+                }
+                float M = -INFINITY;
+#pragma unroll
+                for (int p = 0; p < kMaxParts; p++) M = p < nparts ? fmaxf(M, mp[p]) : M;
+#pragma unroll
+                for (int db = 0; db < DB; db++)
+#pragma unroll
+                    for (int i = 0; i < 16; i++) oacc[db][i] = 0.f;
+                l_tot = 0.f;
+#pragma unroll
+                for (int p = 0; p < kMaxParts; p++) {
+                    if (p < nparts) {
+                        const float w = mp[p] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((mp[p] - M) * a.scale_l2);
+                        split_sum<DB>(a.pq.split_scratch + (int64_t)(slot + p) * kPartialBytes, oacc, w, tid_);
+                        l_tot += w * lp[p];
+                    }
+                }
+                m_run = M;
+            }
+        }
         if (qrow < s && hl == 0) a.lse_out[(int64_t)h * a.T + tok0 + qrow] = m_run * a.scale + __logf(l_tot);
         // O is staged through the K buffers without a barrier: no wavefront reads a K tile after the
         // barrier of the last window (the scores of the last blocks were issued in the window before),

@@ -48,6 +48,7 @@ struct HostPass {
     std::vector<flexsp_item> items;     // queue order
     int64_t offsets[kMaxQueues + 1];    // queue boundaries
     int tile_rows;
+    int32_t records = 0;                // partial-result records of split tiles
 };
 
 struct flexsp_plan {
@@ -83,6 +84,10 @@ int hip_fail(hipError_t e)
 }
 
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Workgroups an attention launch keeps resident: two per compute unit (a host-only context plans
+// for the 256 compute units of the device it stands in for).
+int workgroups_of(const flexsp_ctx *ctx) { return 2 * (ctx->num_cu > 0 ? ctx->num_cu : 256); }
 
 void slab_free(PlanSlab &s)
 {
@@ -189,14 +194,15 @@ struct Work {
     int32_t group;  // (sequence, head) group id
 };
 
-void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int tile_rows, HostPass &out);
+void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int n_wg, int tile_rows,
+                HostPass &out);
 
 // Builds one pass: lists the items, spreads whole (sequence, head) groups over the queues
 // (largest group first onto the least loaded queue, so tiles that read the same K/V run on
 // one XCD and share its L2), then orders each queue by decreasing cost so that the long
 // tail of a batch starts first and short items fill the gaps at the end.
 void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult, int tile_rows,
-                int step_rows, bool causal, bool key_major, int nq, HostPass &out)
+                int step_rows, bool causal, bool key_major, int nq, int n_wg, HostPass &out)
 {
     std::vector<Work> work;
     std::vector<int64_t> group_cost;
@@ -237,12 +243,55 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
             group_cost.push_back(gc);
         }
     }
-    distribute(work, group_cost, nq, tile_rows, out);
+    distribute(work, group_cost, nq, n_wg, tile_rows, out);
+}
+
+// Cuts tiles that would outlast an even share of the pass into parts (see flexsp_item): with W =
+// total steps / workgroups, a tile of c steps becomes ceil(c / max(3W/4, kMinPartSteps)) parts of
+// equal length (at most kMaxParts, none shorter than kMinPartSteps).  Longest-first scheduling alone
+// finishes no earlier than the longest item, which for a batch of few heads and one dominant
+// sequence is several times the even share: the compute units that run out of work wait for it.
+void split_long_items(std::vector<Work> &work, int n_wg, HostPass &out)
+{
+    out.records = 0;
+    int64_t total = 0;
+    for (Work &w : work) {
+        w.it.step_begin = 0;
+        w.it.step_end = (int32_t)w.cost;
+        w.it.slot = -1;
+        w.it.parts = 1;
+        total += w.cost;
+    }
+    const int64_t share = total / std::max(n_wg, 1);
+    const int64_t target = std::max<int64_t>(share * 3 / 4, kMinPartSteps);
+    const size_t n0 = work.size();
+    for (size_t i = 0; i < n0; i++) {
+        const int64_t c = work[i].cost;
+        if (c < 2 * kMinPartSteps || c <= target) continue;
+        int k = (int)std::min<int64_t>(std::min<int64_t>(cdiv(c, target), kMaxParts), c / kMinPartSteps);
+        if (k < 2 || out.records + k > kMaxSplitRecords) continue;
+        const int32_t slot = out.records;
+        out.records += k;
+        for (int p = 0; p < k; p++) {
+            Work w = work[i];
+            w.it.step_begin = (int32_t)((int64_t)p * c / k);
+            w.it.step_end = (int32_t)((int64_t)(p + 1) * c / k);
+            w.it.slot = slot;
+            w.it.parts = (p << 16) | k;
+            w.cost = w.it.step_end - w.it.step_begin;
+            if (p == 0)
+                work[i] = w;
+            else
+                work.push_back(w);
+        }
+    }
 }
 
 // Spreads listed work over the queues and orders every queue longest first (see build_pass).
-void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int tile_rows, HostPass &out)
+void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int n_wg, int tile_rows,
+                HostPass &out)
 {
+    split_long_items(work, n_wg, out);
     // groups -> queues
     std::vector<int32_t> order(group_cost.size());
     for (size_t i = 0; i < order.size(); i++) order[i] = (int32_t)i;
@@ -367,9 +416,18 @@ int plan_upload(flexsp_ctx *ctx, flexsp_plan *p)
             ctr_off[i] = off;
             off = align(off + (nq + 1) * sizeof(int32_t));
         }
+        size_t flag_off[3], part_off[3];
+        for (int i = 0; i < 3; i++) {
+            flag_off[i] = off;
+            off = align(off + (size_t)p->pass[i].records * sizeof(int32_t));
+        }
         size_t head_bytes = off;
         size_t delta_off = off;
         off = align(off + p->delta_bytes + 512);  // the dK/dV kernel reads up to 63 floats past a row's end
+        for (int i = 0; i < 3; i++) {
+            part_off[i] = off;
+            off = align(off + (size_t)p->pass[i].records * kPartialBytes);
+        }
         hipError_t e = hipSetDevice(ctx->device);
         if (e == hipSuccess) e = slab_get(ctx, off ? off : 256, head_bytes ? head_bytes : 256, p->slab);
         if (e != hipSuccess) {
@@ -400,6 +458,8 @@ int plan_upload(flexsp_ctx *ctx, flexsp_plan *p)
             p->dq[i].offsets = (const int32_t *)((char *)p->dev_base + offs_off[i]);
             p->dq[i].counters = (int32_t *)((char *)p->dev_base + ctr_off[i]);
             p->dq[i].nq = nq;
+            p->dq[i].split_flags = (int32_t *)((char *)p->dev_base + flag_off[i]);
+            p->dq[i].split_scratch = (char *)p->dev_base + part_off[i];
         }
         // asynchronous upload on the context's own stream, after the kernels of the slab's previous
         // plan; the hot calls make their stream wait for `ready` (or find it complete already)
@@ -591,10 +651,10 @@ int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu, int32_t B, int32_t Hq
     p->delta_bytes = 2 * (size_t)p->T * Hq * sizeof(float);  // delta and log2-domain LSE, [Hq, T] each
     try {
         p->cu.assign(cu, cu + B + 1);
-        int nq = ctx->num_xcd;
-        build_pass(p->cu, B, Hq, 1, kFwdBq, kFwdBk, causal != 0, false, nq, p->pass[FLEXSP_PASS_FWD]);
-        build_pass(p->cu, B, Hkv, Hq / Hkv, kDkvBk, kDkvBq, causal != 0, true, nq, p->pass[FLEXSP_PASS_BWD_DKV]);
-        build_pass(p->cu, B, Hq, 1, kDqBq, kDqBk, causal != 0, false, nq, p->pass[FLEXSP_PASS_BWD_DQ]);
+        const int nq = ctx->num_xcd, n_wg = workgroups_of(ctx);
+        build_pass(p->cu, B, Hq, 1, kFwdBq, kFwdBk, causal != 0, false, nq, n_wg, p->pass[FLEXSP_PASS_FWD]);
+        build_pass(p->cu, B, Hkv, Hq / Hkv, kDkvBk, kDkvBq, causal != 0, true, nq, n_wg, p->pass[FLEXSP_PASS_BWD_DKV]);
+        build_pass(p->cu, B, Hq, 1, kDqBq, kDqBk, causal != 0, false, nq, n_wg, p->pass[FLEXSP_PASS_BWD_DQ]);
     } catch (const std::bad_alloc &) {
         delete p;
         return FLEXSP_OUT_OF_MEMORY;
@@ -661,7 +721,7 @@ int flexsp_plan_create_kvshard(flexsp_ctx *ctx, const int32_t *cu_q, const int32
                 group_cost.push_back(gc);
             }
         }
-        distribute(work, group_cost, ctx->num_xcd, kFwdBq, p->pass[FLEXSP_PASS_FWD]);
+        distribute(work, group_cost, ctx->num_xcd, 1, kFwdBq, p->pass[FLEXSP_PASS_FWD]);  // (one "workgroup": no tile is cut)
         for (int i = 1; i < 3; i++) {
             for (int x = 0; x <= kMaxQueues; x++) p->pass[i].offsets[x] = 0;
             p->pass[i].tile_rows = 0;

@@ -22,6 +22,16 @@ constexpr int kDkvBq = 64;     // query rows per dK/dV step
 constexpr int kThreads = 256;  // every attention kernel runs 4 wavefronts per workgroup
 constexpr int kMaxQueues = 8;  // one work queue per XCD
 
+// Split tiles (see flexsp_item in flexsp.h): a part's partial result is one record of fp32 values,
+// 64 per thread of the workgroup (the accumulators) plus, for the forward, each row's running
+// maximum and sum.  kMinPartSteps: no part is made shorter than this many inner-loop steps (the
+// hand-over costs about as much as two or three steps); at most kMaxParts parts per tile and
+// kMaxSplitRecords records per pass.
+constexpr int kPartialBytes = 64 * kThreads * 4 + 2 * kThreads * 4;  // 67 584 B
+constexpr int kMinPartSteps = 16;
+constexpr int kMaxParts = 8;
+constexpr int kMaxSplitRecords = 2048;
+
 // Work item of the key-shard forward: query rows q_start .. q_start+q_len-1 of q / o / lse, shard
 // keys k_start .. k_start+k_len-1 of k / v, shift = position of the first query in its sequence
 // minus position of the shard's first key.  `tile` counts 128-row query tiles.
@@ -34,6 +44,8 @@ struct PassQueues {
     const int32_t *offsets;    // device, nq + 1 boundaries into items
     int32_t *counters;         // device, nq fetch counters + 1 "workgroups done" counter
     int32_t nq;
+    int32_t *split_flags;      // device, one arrival counter per partial-result record (a tile uses its first record's)
+    char *split_scratch;       // device, kPartialBytes per record
 };
 
 // Arguments of the attention kernels.  Strides are in elements; pointers already include

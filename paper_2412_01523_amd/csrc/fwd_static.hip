@@ -134,6 +134,11 @@ __global__ __launch_bounds__(kBuildThreads) void build_static_queue_kernel(const
                 it.seq_len = len;
                 it.tile = t;
                 it.head = h;
+                // whole tiles only: every 64-key step the tile's rows can see
+                it.step_begin = 0;
+                it.step_end = ((causal ? min(len, (t + 1) * tile_rows) : len) + kFwdBk - 1) / kFwdBk;
+                it.slot = -1;
+                it.parts = 1;
                 items[x * (total / nq) + min(x, total % nq) + p / nq] = it;
             }
         }

@@ -230,6 +230,35 @@ def test_one_long_sequence_among_short_ones_single_head(ctx):
     _check_case(ctx, "long-among-short", lens, 1, 1, 128, True, 8102)
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,causal", [(2, 2, 128, True), (4, 1, 64, True), (2, 2, 128, False)],
+                         ids=["mha-d128", "gqa-d64", "noncausal"])
+def test_long_tiles_cut_into_parts_and_merged(ctx, Hq, Hkv, D, causal):
+    """One 6 000-token sequence with a few heads next to short ones: the longest tiles would outlast an
+    even share of each pass many times over, so the plan cuts their inner loops into parts that run on
+    different workgroups; each part leaves its partial result in the plan's scratch and the one that
+    finishes last adds them up in part order.  Every element against the oracle in both gradient
+    modes (same bounds as every other case), the plan must really contain cut tiles in all three
+    passes, and three runs must give the same bits whichever part happens to finish last."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    lens = [300, 6000, 1, 200, 129]
+    cu = wl.cu_seqlens(lens)
+    plan = fx.Plan(ctx, cu, Hq, Hkv, D, causal)
+    for which in (fx.PASS_FWD, fx.PASS_BWD_DKV, fx.PASS_BWD_DQ):
+        items, _ = plan.items(which)
+        say(f"  pass {which}: {len(items)} items, {int((items['nparts'] > 1).sum())} of them parts of cut tiles, "
+            f"up to {int(items['nparts'].max())} parts")
+        assert (items["nparts"] > 2).any()
+    plan.close()
+    _check_case(ctx, "cut-tiles", lens, Hq, Hkv, D, causal, 8801)
+    T = sum(lens)
+    q, k, v, g = (wl.normal_bf16(8801, t, (T, h, D)) for t, h in ((wl.TID_Q, Hq), (wl.TID_K, Hkv), (wl.TID_V, Hkv), (wl.TID_DO, Hq)))
+    runs = [GpuAttn(ctx).run(q, k, v, g, cu, causal) for _ in range(3)]
+    for r in runs[1:]:
+        for name in ("O", "LSE", "dQ", "dK", "dV"):
+            assert np.array_equal(r[name], runs[0][name]), f"{name} is not reproducible"
+
+
 def test_explicit_scale_and_plan_reuse_and_determinism(ctx):
     import torch
     from paper_2412_01523_amd import binding as fx

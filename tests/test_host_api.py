@@ -52,18 +52,49 @@ def test_plan_argument_validation(host_ctx):
         assert e.value.status == status
 
 
+def _tile_steps(i, which, causal, rows, group=1):
+    """Inner-loop steps of the TILE an item belongs to: 64-key steps a query tile walks, or 64-query
+    steps (times the heads of the group) a key tile walks."""
+    s, t = int(i["seq_len"]), int(i["tile"])
+    if which == fx.PASS_BWD_DKV:
+        return -(-(s - (t * rows if causal else 0)) // 64) * group
+    return -(-(min(s, (t + 1) * rows) if causal else s) // 64)
+
+
+def _item_steps(i, which, causal, rows, group=1):
+    """Steps of the item itself: part p of k of a tile with n steps covers p*n//k .. (p+1)*n//k - 1."""
+    n, p, k = _tile_steps(i, which, causal, rows, group), int(i["part"]), int(i["nparts"])
+    assert (int(i["step_begin"]), int(i["step_end"])) == (p * n // k, (p + 1) * n // k)
+    return (p + 1) * n // k - p * n // k
+
+
 def _check_pass(plan, which, lens, heads, rows):
     items, offs = plan.items(which)
     cu = wl.cu_seqlens(lens)
-    # every (sequence, tile, head) exactly once
+    # every (sequence, tile, head) is covered: by one whole item, or by parts 0 .. nparts-1 exactly once,
+    # which agree on nparts and on the slot; slots of different tiles do not overlap
     want = set()
     for b, s in enumerate(lens):
         for t in range(-(-s // rows)):
             for h in range(heads):
                 want.add((int(cu[b]), s, t, h))
-    got = [tuple(int(x) for x in it) for it in items]
-    assert len(got) == len(set(got)) == len(want) and set(got) == want
-    assert offs[0] == 0 and offs[-1] == len(got) and (np.diff(offs) >= 0).all()
+    tiles = {}
+    for it in items:
+        key = (int(it["seq_start"]), int(it["seq_len"]), int(it["tile"]), int(it["head"]))
+        tiles.setdefault(key, []).append((int(it["part"]), int(it["nparts"]), int(it["slot"])))
+    assert set(tiles) == want
+    used = []
+    for key, parts in tiles.items():
+        k = parts[0][1]
+        assert sorted(p for p, _, _ in parts) == list(range(k)) and all(n == k for _, n, _ in parts), (key, parts)
+        if k == 1:
+            assert parts[0][2] == -1
+        else:
+            assert 2 <= k <= 8 and len(set(sl for _, _, sl in parts)) == 1 and parts[0][2] >= 0
+            used.append((parts[0][2], parts[0][2] + k))
+    used.sort()
+    assert all(a[1] <= b[0] for a, b in zip(used, used[1:]))
+    assert offs[0] == 0 and offs[-1] == len(items) and (np.diff(offs) >= 0).all()
     return items, offs
 
 
@@ -76,18 +107,21 @@ def test_plan_covers_every_tile_once_longest_first(host_ctx, causal):
     for which, heads in ((fx.PASS_FWD, hq), (fx.PASS_BWD_DKV, hkv), (fx.PASS_BWD_DQ, hq)):
         rows = plan.tile_rows(which)
         items, offs = _check_pass(plan, which, live if False else lens, heads, rows)
-        # inside a queue: cost never increases.  cost of a query tile = keys it reads;
-        # of a key tile = query rows that read it.
+        # inside a queue: cost (inner-loop steps of the item) never increases
         for x in range(len(offs) - 1):
-            seg = items[offs[x]:offs[x + 1]]
-            if which == fx.PASS_BWD_DKV:
-                cost = [(int(i["seq_len"]) - (int(i["tile"]) * rows if causal else 0)) for i in seg]
-                step = 64
-            else:
-                cost = [min(int(i["seq_len"]), (int(i["tile"]) + 1) * rows) if causal else int(i["seq_len"]) for i in seg]
-                step = 64
-            steps = [-(-c // step) for c in cost]
+            steps = [_item_steps(i, which, causal, rows, hq // hkv) for i in items[offs[x]:offs[x + 1]]]
             assert all(a >= b for a, b in zip(steps, steps[1:]))
+        # tiles are cut when, and only when, they would outlast 3/4 of an even share of the pass over the
+        # 512 workgroups a host-only context plans for; no part is shorter than 16 steps
+        total = sum(_item_steps(i, which, causal, rows, hq // hkv) for i in items)
+        target = max(total // 512 * 3 // 4, 16)
+        for i in items:
+            n = _tile_steps(i, which, causal, rows, hq // hkv)
+            if int(i["nparts"]) > 1:
+                assert n > target and n >= 32 and _item_steps(i, which, causal, rows, hq // hkv) >= 16
+                assert int(i["nparts"]) == min(-(-n // target), 8, n // 16)
+            else:
+                assert n <= target or n < 32
         # a (sequence, head) group stays on one queue (one XCD, one L2) unless levelling the queues
         # had to move some of its cheapest tiles: most groups are whole
         owner = {}
@@ -108,7 +142,7 @@ def test_plan_balances_queues_on_the_long_tail_config(host_ctx):
     load = []
     for x in range(8):
         seg = items[offs[x]:offs[x + 1]]
-        load.append(sum(-(-min(int(i["seq_len"]), (int(i["tile"]) + 1) * rows) // 64) for i in seg))
+        load.append(sum(_item_steps(i, fx.PASS_FWD, True, rows) for i in seg))
     assert max(load) <= 1.01 * (sum(load) / 8) + 2
     # the very first item of each queue is one of the longest tiles of the batch
     longest = max(lens)
@@ -125,8 +159,7 @@ def test_plan_levels_queues_when_one_sequence_dominates(host_ctx):
     for which, step in ((fx.PASS_FWD, 64), (fx.PASS_BWD_DQ, 64)):
         items, offs = plan.items(which)
         rows = plan.tile_rows(which)
-        load = [sum(-(-min(int(i["seq_len"]), (int(i["tile"]) + 1) * rows) // step) for i in items[offs[x]:offs[x + 1]])
-                for x in range(8)]
+        load = [sum(_item_steps(i, which, True, rows) for i in items[offs[x]:offs[x + 1]]) for x in range(8)]
         assert max(load) - min(load) <= max(-(-max(lens) // step), 4), load
     plan.close()
 
@@ -140,8 +173,8 @@ def test_plan_with_few_enormous_items_takes_the_comparison_sort_path(host_ctx):
     for which, heads in ((fx.PASS_FWD, 16), (fx.PASS_BWD_DKV, 1), (fx.PASS_BWD_DQ, 16)):
         rows = plan.tile_rows(which)
         items, offs = _check_pass(plan, which, lens, heads, rows)
-        for x in range(len(offs) - 1):   # cost = the sequence's length here (every tile sees every row)
-            seg = [int(i["seq_len"]) for i in items[offs[x]:offs[x + 1]]]
+        for x in range(len(offs) - 1):
+            seg = [_item_steps(i, which, False, rows, 16) for i in items[offs[x]:offs[x + 1]]]
             assert all(a >= b for a, b in zip(seg, seg[1:]))
         sizes = np.diff(offs)
         assert sizes.max() - sizes.min() <= 2 + len(lens) * heads   # equal-cost items: queues level out

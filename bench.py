@@ -24,6 +24,7 @@ workload (a reported baseline, not a target).
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -41,8 +42,8 @@ HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 # counter values and the algorithmic bytes beside them are in profiles/attention_hbm_traffic.md).
 # bench.py cannot run the profiler on itself: these are the figures of that summary.
 MEASURED_HBM_TRAFFIC = {
-    ("pareto-64k", "fwd"): 1313768630, ("pareto-64k", "bwd_dq"): 1623344037, ("pareto-64k", "bwd_dkv"): 1842422372,
-    ("single-128k", "fwd"): 42790452858, ("single-128k", "bwd_dq"): 73218150768, ("single-128k", "bwd_dkv"): 22220939311,
+    ("pareto-64k", "fwd"): 1335123598, ("pareto-64k", "bwd_dq"): 1654770128, ("pareto-64k", "bwd_dkv"): 1934074213,
+    ("single-128k", "fwd"): 38718101061, ("single-128k", "bwd_dq"): 75643124185, ("single-128k", "bwd_dkv"): 81196837586,
 }
 
 
@@ -243,6 +244,8 @@ def main() -> int:
     # (the library's per-kernel event recorder is OFF here; one stream marker per step gives the
     # per-step minimum and median)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    gc.collect()
+    gc.disable()     # a collection of the interpreter's heap in the middle of a step stalls the host for milliseconds
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     marks[0].record(stream)
@@ -251,6 +254,7 @@ def main() -> int:
         marks[i + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    gc.enable()
     ms_step = (t1 - t0) * 1e3 / max(args.steps, 1)
     per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
 
@@ -329,6 +333,8 @@ def main() -> int:
             torch.cuda.synchronize()
             n_k = 20
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_k + 1)]
+            gc.collect()
+            gc.disable()
             ts0 = time.perf_counter()
             ev[0].record(stream)
             for i in range(n_k):
@@ -336,6 +342,7 @@ def main() -> int:
                 ev[i + 1].record(stream)
             torch.cuda.synchronize()
             ms_k = (time.perf_counter() - ts0) * 1e3 / n_k
+            gc.enable()
             each = [ev[i].elapsed_time(ev[i + 1]) for i in range(n_k)]
             med = float(np.median(each))
             legs.append({"length_seed": cfg.seed + k_, "sequences": len(lens_k), "max_len": max(lens_k),

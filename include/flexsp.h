@@ -88,17 +88,20 @@ int flexsp_ctx_num_xcd(const flexsp_ctx *ctx);
  *                    reads kv head h / (Hq/Hkv)).
  *   D                head dim, 64 or 128.
  *   causal           nonzero: key j of a sequence is visible to query i iff j <= i.
- * The plan lists work items (sequence, tile, head), longest first, in one queue per XCD,
- * for the forward kernel and for the two backward kernels, and holds the fp32 scratch
- * (delta [Hq, T]) the backward needs, so the hot calls allocate nothing.
+ * The plan lists work items (sequence, tile, head; the longest tiles cut into parts when few
+ * heads and a dominant sequence would leave compute units waiting for them, see flexsp_item),
+ * longest first, in one queue per XCD, for the forward kernel and for the two backward kernels,
+ * and holds the fp32 scratch the kernels need (delta and the base-2 log-sum-exp [Hq, T] for the
+ * backward, one 66 KiB record per part of a cut tile), so the hot calls allocate nothing.
  * Everything is copied before the call returns; the caller keeps ownership of
  * cu_seqlens_host.  On a device context the queues go to the GPU with an asynchronous copy on
  * a stream of the context's own, and the first forward / backward call that uses the plan
  * makes its stream wait for that copy (a call made under stream capture should find the copy
  * finished: create the plan, let work that follows it complete, then capture).  Device and
  * pinned memory of destroyed plans is kept by the context (up to 8 buffers) and handed to new
- * plans, ordered after the kernels that still use it, so a plan per micro-batch costs neither
- * an allocation nor a device-wide synchronisation.  A context, and the plans made from it,
+ * plans, ordered after the kernels that still use it (a buffer whose kernels have finished is
+ * preferred; a context makes at most three before it reuses a busy one), so a plan per
+ * micro-batch costs neither an allocation nor a device-wide synchronisation after the first steps.  A context, and the plans made from it,
  * belong to one host thread at a time.
  * Errors: INVALID_ARGUMENT, UNSUPPORTED (D), OUT_OF_MEMORY, HIP_ERROR.
  */

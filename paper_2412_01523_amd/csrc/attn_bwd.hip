@@ -123,20 +123,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
         if (n > 0) prefetch(h_cur, q_cur, 0);
         advance_nxt();
 
-        // K and V fragments of the pair's 32 keys (B operands: column = key, k = head dim)
+        // K and V fragments of the pair's 32 keys (B operands: column = key, k = head dim), through
+        // this wavefront's quarter of tile buffer 1, which is idle until step 0 requests step 1's tiles
         bf16x8 kf[KS], vf[KS];
         {
-            const bool ok = kvrow < s;
-            const uint16_t *kp = a.k + (tok0 + (ok ? kvrow : 0)) * a.k_st + (int64_t)g * a.k_sh + 8 * hl;
-            const uint16_t *vp = a.v + (tok0 + (ok ? kvrow : 0)) * a.v_st + (int64_t)g * a.v_sh + 8 * hl;
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-                Frag8 f;
-                f.u = ok ? *(const u32x4 *)(kp + 16 * ks) : u32x4{0, 0, 0, 0};
-                kf[ks] = f.v;
-                f.u = ok ? *(const u32x4 *)(vp + 16 * ks) : u32x4{0, 0, 0, 0};
-                vf[ks] = f.v;
-            }
+            RowBlock<D> krows, vrows;
+            krows.load(a.k + tok0 * a.k_st + (int64_t)g * a.k_sh, a.k_st, wk_lo, s - 1, lane);
+            vrows.load(a.v + tok0 * a.v_st + (int64_t)g * a.v_sh, a.v_st, wk_lo, s - 1, lane);
+            // (this kernel's fragment offsets point at row block j of a tile: wavefronts 2kb and 2kb+1 use
+            // the two halves of one 64-row stretch, so the stretch's address serves both)
+            char *stretch = smem + STEP + kb * (64 * L::ROWB);
+            krows.fragments(stretch, j * 32, lo, kf, lane);
+            vrows.fragments(stretch, j * 32, lo, vf, lane);
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): in registers before step 0's barrier frees the buffer
         }
         f32x16 accT[DB];  // dV^T (role 0) or dK^T (role 1): rows = head dim, column = key
 #pragma unroll
@@ -324,7 +323,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
     ItemDealer deal;
 
     for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
-        deal.prefetch();
         const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
@@ -363,29 +361,27 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         // has the row's dO in registers anyway): this lane's half of the row, then the other half-wave's
         float dpart = 0.f;
         {
-            const uint16_t *qp = a.q + (tok0 + (qok ? qrow : 0)) * a.q_st + (int64_t)h * a.q_sh + 8 * hl;
-            const uint16_t *gp = a.dO + (tok0 + (qok ? qrow : 0)) * a.do_st + (int64_t)h * a.do_sh + 8 * hl;
-            const uint16_t *op = a.o + (tok0 + (qok ? qrow : 0)) * a.o_st + (int64_t)h * a.o_sh + 8 * hl;
-            // all loads first, then the arithmetic (the file is compiled in source order: a dot product
-            // between two loads would make the second wait for the first)
-            u32x4 ov[KS];
+            // the three row blocks are requested together and pass one after the other through this
+            // wavefront's quarter of tile buffer 1, which is idle until step 0 requests tile 1
+            RowBlock<D> qrows, grows, orows;
+            qrows.load(a.q + tok0 * a.q_st + (int64_t)h * a.q_sh, a.q_st, wq_lo, s - 1, lane);
+            grows.load(a.dO + tok0 * a.do_st + (int64_t)h * a.do_sh, a.do_st, wq_lo, s - 1, lane);
+            orows.load(a.o + tok0 * a.o_st + (int64_t)h * a.o_sh, a.o_st, wq_lo, s - 1, lane);
+            char *region = smem + 2 * TILE + wave * (32 * L::ROWB);
+            bf16x8 of[KS];
+            qrows.fragments(region, 0, lo, qf, lane);
+            grows.fragments(region, 0, lo, gf, lane);
+            orows.fragments(region, 0, lo, of, lane);
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): in registers before step 0's barrier frees the buffer
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) {
-                Frag8 f;
-                f.u = qok ? *(const u32x4 *)(qp + 16 * ks) : u32x4{0, 0, 0, 0};
-                qf[ks] = f.v;
-                f.u = qok ? *(const u32x4 *)(gp + 16 * ks) : u32x4{0, 0, 0, 0};
-                gf[ks] = f.v;
-                ov[ks] = qok ? *(const u32x4 *)(op + 16 * ks) : u32x4{0, 0, 0, 0};
-            }
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-                Frag8 f;
-                f.v = gf[ks];
+                Frag8 fg, fo;
+                fg.v = gf[ks];
+                fo.v = of[ks];
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
                     // (scalars first: a bit cast applied to a vector element in place reads element 0)
-                    const uint32_t gw = f.u[i], ow = ov[ks][i];
+                    const uint32_t gw = fg.u[i], ow = fo.u[i];
                     dpart = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, gw), __builtin_bit_cast(bf16x2, ow),
                                                             dpart, false);
                 }
@@ -410,6 +406,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
             lo.pin();
             wait_vmem();
             __syncthreads();
+            // the next item's ticket is drawn behind the first wait: answers come back in request order, and
+            // in front of the item's first loads the counter's round trip would hold them up
+            if (t == 0) deal.prefetch();
             if (__builtin_expect(t + 1 < ntiles, 1)) prefetch(t + 1, BUF ^ 1);
             if (a.causal && kv0 > wq_rel + 31) return;
 
@@ -477,6 +476,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                 }
             }
         };
+        if (ntiles <= 0) deal.prefetch();
         for (int t = 0; t < ntiles; t += 2) {
             step_fn(std::integral_constant<int, 0>{}, t);
             if (t + 1 < ntiles) step_fn(std::integral_constant<int, 1>{}, t + 1);

@@ -230,6 +230,49 @@ __device__ __forceinline__ bf16x8 lds_tr(const char *tile, int off0, int off1)
     return f.v;
 }
 
+// 32 consecutive rows of a row-major global matrix (D bf16 each) as the operand fragments of a
+// wavefront: f[ks] of lane (r = l % 32, hl = l / 32) holds elements 16*ks + 8*hl .. +7 of row r.
+// Loading a fragment straight from global memory makes every lane of an instruction touch a
+// different row (32 rows, 32 bytes of each): the load path takes such an instruction apart lane by
+// lane, and the 8 (D = 128) of them per operand cost a wavefront microseconds at the start of every
+// work item.  Here the rows are read with whole-row instructions (lane l of piece n reads 16-byte
+// chunk (64n + l) % CH of row (64n + l) / CH: 1 KiB contiguous per instruction for D = 128) and
+// turned into fragments through a wave-private LDS region of 32 rows, laid out like a tile.
+// Rows past `last_valid` duplicate that row (finite data; callers never store their results).
+template <int D>
+struct RowBlock {
+    typedef LdsTile<D> L;
+    static constexpr int N = 32 * L::CH / 64;  // 16-byte pieces per lane
+    u32x4 raw[N];
+    // g: row 0 of the sequence at the wanted head; issues the loads, waits for nothing
+    __device__ __forceinline__ void load(const uint16_t *g, int64_t stride, int first, int last_valid, int lane)
+    {
+#pragma unroll
+        for (int n = 0; n < N; n++) {
+            const int pos = n * 64 + lane;
+            const int row = min(first + pos / L::CH, last_valid);
+            raw[n] = *(const u32x4 *)(g + (int64_t)row * stride + (pos % L::CH) * 8);
+        }
+    }
+    // The block is kept in rows row0 .. row0+31 (row0 a multiple of 32) of the tile-shaped LDS area
+    // `tile`, which nobody else touches until this wavefront's next barrier; lo.nat must point at
+    // those rows of a tile (kernels that fold a row offset into lo.nat pass the same offset here).
+    __device__ __forceinline__ void fragments(char *tile, int row0, const LaneOffsets<D> &lo, bf16x8 (&f)[D / 16], int lane)
+    {
+        char *region = tile + row0 * L::ROWB;
+#pragma unroll
+        for (int n = 0; n < N; n++) {
+            const int pos = n * 64 + lane;
+            const int row = pos / L::CH;
+            *(u32x4 *)(region + row * L::ROWB + (((pos % L::CH) ^ L::sw(row)) << 4)) = raw[n];
+        }
+        // (LDS instructions of one wavefront execute in order: the reads see the writes, and a later
+        // call's writes to the same region come after these reads)
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ks++) f[ks] = lds_nat(tile, lo.nat[ks]);
+    }
+};
+
 // max / sum across the two half-waves: every lane gets op(x[l % 32], x[l % 32 + 32]).
 // v_permlane32_swap exchanges the upper half of its first operand with the lower half of its
 // second; fed the same value twice it returns {x[l % 32], x[l % 32 + 32]} in every lane.

@@ -59,7 +59,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
 
     int item = deal.first(a.pq, &deal_word, wave, lane0);
     for (; item >= 0; item = deal.advance()) {
-        deal.prefetch();
         // s: query rows of the sequence; sk: its keys; tok0 / ktok0: their first rows in q / k, v
         int s, sk, shift, h, q0;
         int64_t tok0, ktok0;
@@ -107,6 +106,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                             u32x4{0, 0, 0, 0};
                 }
                 if (tid < kFwdBq && q0 + tid < s) a.lse_out[(int64_t)h * a.T + tok0 + q0 + tid] = -INFINITY;
+                deal.prefetch();
                 continue;
             }
         }
@@ -132,20 +132,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         };
         prefetch_k(0, 0);
 
-        // ---- Q fragments (B operand: column = query row, k = head dim), kept in registers
+        // ---- Q fragments (B operand: column = query row, k = head dim), kept in registers: the rows
+        // are requested here and become fragments just before the barrier below
         const int qrow = q0 + wave * 32 + r;  // row inside the sequence
         const int wq_lo = q0 + wave * 32;     // smallest query row of this wavefront
+        RowBlock<D> qrows;
+        qrows.load(a.q + tok0 * a.q_st + (int64_t)h * a.q_sh, a.q_st, wq_lo, s - 1, lane);
         bf16x8 qf[KS];
-        {
-            const bool ok = qrow < s;
-            const uint16_t *qp = a.q + (tok0 + (ok ? qrow : 0)) * a.q_st + (int64_t)h * a.q_sh + 8 * hl;
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-                Frag8 f;
-                f.u = ok ? *(const u32x4 *)(qp + 16 * ks) : u32x4{0, 0, 0, 0};
-                qf[ks] = f.v;
-            }
-        }
         // last 32-key block this wavefront has to look at (-1: none, its rows lie past the sequence)
         int cmax, cmask, lim;
         if constexpr (SHARD) {
@@ -346,8 +339,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         };
 
         // ---------------- pipeline fill: K tile 0 -> S(0), then iteration 0 --------------------
+        // (the Q rows pass through this wavefront's quarter of the V buffers, which are idle until the
+        // barrier: V tile 0 is requested after it)
+        qrows.fragments(smem + 2 * TILE + wave * (32 * L::ROWB), 0, lo, qf, lane);
         wait_vmem();
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the fragments are in registers
         __syncthreads();
+        // The ticket of the item after this one is drawn here, not when the item starts: answers come
+        // back in the order of the requests, so the wait for the item's first loads would also be a
+        // wait for the counter's round trip, which is several times longer.
+        deal.prefetch();
         if (ntiles > 1) prefetch_k(1, 1);
         prefetch_v(0, 0);
         if (cmax >= 0) scores(sacc[0], smem);

@@ -238,21 +238,26 @@ __device__ __forceinline__ bf16x8 lds_tr(const char *tile, int off0, int off1)
 // work item.  Here the rows are read with whole-row instructions (lane l of piece n reads 16-byte
 // chunk (64n + l) % CH of row (64n + l) / CH: 1 KiB contiguous per instruction for D = 128) and
 // turned into fragments through a wave-private LDS region of 32 rows, laid out like a tile.
-// Rows past `last_valid` duplicate that row (finite data; callers never store their results).
+// Rows past `last_valid` read as zeros (callers never store their results).
 template <int D>
 struct RowBlock {
     typedef LdsTile<D> L;
     static constexpr int N = 32 * L::CH / 64;  // 16-byte pieces per lane
     u32x4 raw[N];
-    // g: row 0 of the sequence at the wanted head; issues the loads, waits for nothing
+    // g: row 0 of the sequence at the wanted head (wave-uniform, like first and last_valid); issues
+    // the loads, waits for nothing.  Buffer loads: one wave-uniform descriptor of the block (its first
+    // row's address, the bytes up to the end of the sequence) and one per-lane byte offset serve all
+    // pieces, so there is no per-lane 64-bit address arithmetic, and the bounds check of the hardware
+    // returns zeros for rows past the sequence.
     __device__ __forceinline__ void load(const uint16_t *g, int64_t stride, int first, int last_valid, int lane)
     {
+        const int nrows = min(last_valid - first + 1, 32);
+        const uint32_t rowb = (uint32_t)stride * 2u;  // bytes from row to row
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(g + (int64_t)first * stride), 0, nrows > 0 ? (int)(nrows * rowb) : 0, 0x00020000);
+        const uint32_t off = (uint32_t)(lane / L::CH) * rowb + (uint32_t)(lane % L::CH) * 16u;
 #pragma unroll
-        for (int n = 0; n < N; n++) {
-            const int pos = n * 64 + lane;
-            const int row = min(first + pos / L::CH, last_valid);
-            raw[n] = *(const u32x4 *)(g + (int64_t)row * stride + (pos % L::CH) * 8);
-        }
+        for (int n = 0; n < N; n++) raw[n] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, n * (64 / L::CH) * rowb, 0);
     }
     // The block is kept in rows row0 .. row0+31 (row0 a multiple of 32) of the tile-shaped LDS area
     // `tile`, which nobody else touches until this wavefront's next barrier; lo.nat must point at
@@ -480,24 +485,48 @@ __device__ __forceinline__ flexsp_shard_item load_shard_item(const flexsp_shard_
 // a plan's counters must not overlap.
 struct ItemDealer {
     const int32_t *offsets;
-    int32_t *counters;  // [nq] tickets drawn beyond the static ones, [nq] = workgroups that left
+    int32_t *counters;  // kCounterStride apart (a line of their own each: they are hammered from all
+                        // compute dies at once): [q] tickets drawn beyond the static ones, [nq] workgroups that left
     int *slot;          // LDS word
-    int nq, q, hops, wave, lane;
+    int nq, q, wave, lane;
     int pending;        // wavefront 0, lane 0: ticket drawn ahead (offset from W of queue q)
 
     __device__ __forceinline__ int wgs_of(int qq) const { return ((int)gridDim.x - qq + nq - 1) / nq; }
     __device__ __forceinline__ int draw(int qq)  // wavefront 0 only; waits for the answer
     {
         int tk = 0;
-        if (lane == 0) tk = atomicAdd(counters + qq, 1);
+        if (lane == 0) tk = atomicAdd(counters + qq * kCounterStride, 1);
         return __builtin_amdgcn_readfirstlane(tk);
     }
-    // wavefront 0: first item of the other queues, in ring order, or -1 when all are empty
+    // wavefront 0: an item of another queue, or -1 when all are empty.  Looks before it draws: one
+    // load of all counters, then a ticket from the queue with the most items left (ties: the next in
+    // ring order), again if somebody else emptied that queue meanwhile.  Drawing from the queues one
+    // after the other instead made every leaving workgroup send a read-modify-write to every
+    // counter: at the end of a pass thousands of them queue up on a handful of addresses, and the
+    // loads of the items still running wait behind them (their last items took twice as long).
     __device__ __forceinline__ int steal()
     {
-        while (hops < nq - 1) {
-            hops++;
-            q = q + 1 == nq ? 0 : q + 1;
+        // (every failed try means that another workgroup emptied a queue in between, so the tries
+        // end by themselves; the bound is a belt to the braces)
+        for (int tries = 0; tries < 4 * kMaxQueues; tries++) {
+            // lanes 0 .. nq-1 (nq <= 8) look at one queue each; the key orders the queues by items left,
+            // then by ring distance from this workgroup's queue, and carries the queue's number
+            int l = lane;
+            asm volatile("" : "+v"(l));  // (keeps this arithmetic here: it is loop-invariant and would be hoisted into long-lived registers)
+            int key = 0;
+            if (l < nq) {
+                const int drawn = __hip_atomic_load(counters + l * kCounterStride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int left = offsets[l + 1] - offsets[l] - wgs_of(l) - drawn;
+                const int dist = l > q ? l - q : l - q + nq;  // 1 .. nq
+                key = left > 0 ? (min(left, 0xFFFFF) << 8) | ((8 - dist) << 4) | l : 0;
+            }
+            // maximum over lanes 0 .. 7: lane ^ 1, lane ^ 2, then the mirrored half row
+            key = max(key, __builtin_amdgcn_update_dpp(0, key, 0xB1, 0xF, 0xF, true));
+            key = max(key, __builtin_amdgcn_update_dpp(0, key, 0x4E, 0xF, 0xF, true));
+            key = max(key, __builtin_amdgcn_update_dpp(0, key, 0x141, 0xF, 0xF, true));
+            key = __builtin_amdgcn_readfirstlane(key);
+            if (key == 0) return -1;
+            q = key & 15;
             const int idx = offsets[q] + wgs_of(q) + draw(q);
             if (idx < offsets[q + 1]) return idx;
         }
@@ -521,7 +550,6 @@ struct ItemDealer {
         wave = wave_;
         lane = lane_;
         q = (int)(blockIdx.x % pq.nq);
-        hops = 0;
         pending = 0;
         int idx = -1;
         if (wave == 0) {
@@ -533,7 +561,7 @@ struct ItemDealer {
     // call when an item starts: draws the ticket of the item after it
     __device__ __forceinline__ void prefetch()
     {
-        if (wave == 0 && lane == 0) pending = atomicAdd(counters + q, 1);
+        if (wave == 0 && lane == 0) pending = atomicAdd(counters + q * kCounterStride, 1);
     }
     // call when an item is done (all of the workgroup's LDS reads issued): next item or -1
     __device__ __forceinline__ int advance()
@@ -546,14 +574,16 @@ struct ItemDealer {
         return publish(idx);
     }
     // call once, after the last item
+    // The last workgroup to leave clears the counters for the next launch.  No fence: every ticket a
+    // workgroup drew has come back before it gets here (it used the values), this counter's own
+    // atomic orders the workgroups, and the clearing stores go to memory like the atomics do.  (A
+    // device-scope fence writes back and invalidates the L2 of the compute die it runs on, once per
+    // leaving workgroup: the workgroups still running then find their tiles gone from the cache.)
     __device__ __forceinline__ void finish()
     {
         if (wave == 0 && lane == 0) {
-            __threadfence();
-            if (atomicAdd(counters + nq, 1) == (int)gridDim.x - 1) {
-                for (int i = 0; i <= nq; i++) counters[i] = 0;
-                __threadfence();
-            }
+            if (atomicAdd(counters + nq * kCounterStride, 1) == (int)gridDim.x - 1)
+                for (int i = 0; i <= nq; i++) __hip_atomic_store(counters + i * kCounterStride, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 };

@@ -414,7 +414,7 @@ int plan_upload(flexsp_ctx *ctx, flexsp_plan *p)
         }
         for (int i = 0; i < 3; i++) {
             ctr_off[i] = off;
-            off = align(off + (nq + 1) * sizeof(int32_t));
+            off = align(off + (nq + 1) * kCounterStride * sizeof(int32_t));
         }
         size_t flag_off[3], part_off[3];
         for (int i = 0; i < 3; i++) {

@@ -21,6 +21,7 @@ constexpr int kDkvBk = 64;     // key rows per dK/dV work item (2 pairs of waves
 constexpr int kDkvBq = 64;     // query rows per dK/dV step
 constexpr int kThreads = 256;  // every attention kernel runs 4 wavefronts per workgroup
 constexpr int kMaxQueues = 8;  // one work queue per XCD
+constexpr int kCounterStride = 32;  // int32 from one queue's ticket counter to the next: a 128-byte line each
 
 // Split tiles (see flexsp_item in flexsp.h): a part's partial result is one record of fp32 values,
 // 64 per thread of the workgroup (the accumulators) plus, for the forward, each row's running
@@ -42,7 +43,7 @@ struct flexsp_shard_item {
 struct PassQueues {
     const flexsp_item *items;  // device, all queues back to back
     const int32_t *offsets;    // device, nq + 1 boundaries into items
-    int32_t *counters;         // device, nq fetch counters + 1 "workgroups done" counter
+    int32_t *counters;         // device, nq fetch counters + 1 "workgroups done" counter, kCounterStride apart
     int32_t nq;
     int32_t *split_flags;      // device, one arrival counter per partial-result record (a tile uses its first record's)
     char *split_scratch;       // device, kPartialBytes per record

@@ -14,10 +14,10 @@ namespace {
 // ---------------------------------------------------------------------------- the scratch
 constexpr int kStaticMaxItems = 65536;   // work items (128 query rows of one head each) per call
 constexpr int kStaticMaxLevels = 4096;   // query tiles per sequence: sequences up to 524 288 tokens
-constexpr int kCountersOff = 0;          // int32[16]: kMaxQueues ticket counters + "workgroups done"
-constexpr int kOffsetsOff = 64;          // int32[16]: kMaxQueues + 1 queue boundaries
-constexpr int kStatusOff = 128;          // int32[2]: items listed by the last call, 1 if its lengths were rejected
-constexpr int kItemsOff = 256;
+constexpr int kCountersOff = 0;          // kMaxQueues ticket counters + "workgroups done", kCounterStride int32 apart
+constexpr int kOffsetsOff = (kMaxQueues + 1) * kCounterStride * 4;  // int32[16]: kMaxQueues + 1 queue boundaries
+constexpr int kStatusOff = kOffsetsOff + 64;  // int32[2]: items listed by the last call, 1 if its lengths were rejected
+constexpr int kItemsOff = kStatusOff + 64;
 constexpr size_t kScratchBytes = kItemsOff + (size_t)kStaticMaxItems * sizeof(flexsp_item);
 
 // One copy per GPU, at its own address.  In host code this name is only a handle for
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kBuildThreads) void build_static_queue_kernel(const
         s_bad = (B > 0 && cu[0] != 0) ? 1 : 0;
         s_total = 0;
     }
-    if (tid <= kMaxQueues) counters[tid] = 0;  // every call starts with clear tickets
+    if (tid <= kMaxQueues) counters[tid * kCounterStride] = 0;  // every call starts with clear tickets
     __syncthreads();
 
     for (int b = tid; b < B; b += kBuildThreads) {

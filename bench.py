@@ -236,6 +236,12 @@ def main() -> int:
         for x, s in ((xq, sq), (xk, sk), (xv, sv), (xg, sg)):
             fx.flexsp_pack(ctx, x, s, P, stream)
 
+    # (a collection of the interpreter's heap in the middle of a step stalls the host for milliseconds;
+    # collected once BEFORE the warm-up, so that nothing but the synchronisation lies between the
+    # warm-up and the timed steps: the GPU's clocks drop while it waits for the host)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    gc.collect()
+    gc.disable()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -243,15 +249,13 @@ def main() -> int:
     # ---- the timed region: K steps, nothing but the path itself between the two synchronisations
     # (the library's per-kernel event recorder is OFF here; one stream marker per step gives the
     # per-step minimum and median)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    gc.collect()
-    gc.disable()     # a collection of the interpreter's heap in the middle of a step stalls the host for milliseconds
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
     marks[0].record(stream)
+    host_t = [t0]
     for i in range(args.steps):
         step()
         marks[i + 1].record(stream)
+        host_t.append(time.perf_counter())
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     gc.enable()
@@ -310,6 +314,7 @@ def main() -> int:
 
     if os.environ.get("BENCH_DUMP_STEPS"):
         out["per_step"] = per_step
+        out["per_step_host_enqueue_ms"] = [(b - a_) * 1e3 for a_, b in zip(host_t, host_t[1:])]
     if not args.no_permute_leg:
         out["permute"] = permute_leg(ctx, fx, wl, torch, stream)
 
@@ -328,13 +333,13 @@ def main() -> int:
                 fx.flexsp_attn_varlen_bwd(ctx, plan, v3(sq), v3(sk), v3(sv), v3(so), v3(sg), lse, cud_k,
                                           v3(sdq), v3(sdk), v3(sdv), stream=stream)
                 plan.close()
-            for _ in range(10):
-                attn_step()
-            torch.cuda.synchronize()
             n_k = 20
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_k + 1)]
             gc.collect()
             gc.disable()
+            for _ in range(10):
+                attn_step()
+            torch.cuda.synchronize()
             ts0 = time.perf_counter()
             ev[0].record(stream)
             for i in range(n_k):

@@ -27,8 +27,9 @@ struct PlanSlab {
     hipEvent_t done = nullptr;   // recorded on the last stream that ran kernels on this slab
     bool done_valid = false;
 };
-constexpr size_t kSlabPoolMax = 8;  // free slabs kept by a context
-constexpr size_t kSlabEager = 3;    // slabs a context makes rather than wait for a busy one
+constexpr size_t kSlabPoolMax = 16;  // free slabs kept by a context
+constexpr size_t kSlabEager = 4;     // slabs a context makes rather than wait for a busy one ...
+constexpr size_t kSlabEagerBytes = (size_t)1 << 30;  // ... while they hold less device memory than this
 
 struct flexsp_ctx {
     int device;  // -1: host-only
@@ -37,6 +38,7 @@ struct flexsp_ctx {
     hipStream_t upload = nullptr;  // non-blocking stream (default priority) for plan uploads
     std::vector<PlanSlab> slabs;   // free slabs
     size_t slabs_owned = 0;        // slabs alive: free ones and those held by plans
+    size_t slab_bytes = 0;         // device memory of the slabs alive
     // profiling: a pool of event pairs created by flexsp_profile_start
     bool profiling;
     std::vector<EventPair> events;
@@ -103,11 +105,16 @@ void slab_free(PlanSlab &s)
 // once, while the kernels of the plan destroyed a moment ago still run.  Taking back the slab just
 // released instead would put every step's upload behind the previous step's last kernel and in
 // front of its own first one, an idle gap per step.  When every adequate slab is still in use
-// and the context owns fewer than kSlabEager, a new one is made (a quarter larger than asked, so
-// that the next, slightly different batch fits too); allocating device and pinned memory takes
-// milliseconds and disturbs running kernels, so it is confined to the first steps of a run: a plan
-// per micro-batch settles on kSlabEager slabs taken in turn.  Beyond that a busy slab is taken,
-// the one released longest ago, ordered after its kernels by its event.
+// and the context owns fewer than kSlabEager slabs (and less than kSlabEagerBytes in them), a new one
+// is made (a quarter larger than asked, so that the next, slightly different batch fits too).
+// Beyond that the HOST waits here for the busy slab released longest ago: a caller that builds a
+// plan per micro-batch is thereby held kSlabEager steps ahead of the GPU at most, which keeps the
+// GPU fed just as well as running ahead without bound does.  Both alternatives were measured and
+// stall the GPU for 6-9 ms each time: making slabs as the host runs further ahead (allocating
+// device and pinned memory in the middle of a run), and ordering the upload behind the busy
+// slab's kernels with an event on the upload stream (the first such cross-stream waits after an
+// idle period).  With the host-side wait, allocations end with the first kSlabEager plans of a run
+// and no stream ever waits for an event that is not complete yet.
 hipError_t slab_get(flexsp_ctx *ctx, size_t dev_bytes, size_t host_bytes, PlanSlab &out)
 {
     int best = -1, best_busy = -1;
@@ -122,10 +129,16 @@ hipError_t slab_get(flexsp_ctx *ctx, size_t dev_bytes, size_t host_bytes, PlanSl
             best_busy = (int)i;
         }
     }
-    if (best < 0 && best_busy >= 0 && ctx->slabs_owned >= kSlabEager) best = best_busy;
+    if (best < 0 && best_busy >= 0 && (ctx->slabs_owned >= kSlabEager || ctx->slab_bytes + dev_bytes > kSlabEagerBytes))
+        best = best_busy;
     if (best >= 0) {
         out = ctx->slabs[best];
         ctx->slabs.erase(ctx->slabs.begin() + best);
+        if (best == best_busy) {
+            hipError_t e = hipEventSynchronize(out.done);
+            if (e != hipSuccess) return e;
+        }
+        out.done_valid = false;  // its kernels are over: nothing to order the upload behind
         // the previous upload from this pinned buffer must be over before the host refills it
         return hipEventSynchronize(out.ready);
     }
@@ -141,6 +154,7 @@ hipError_t slab_get(flexsp_ctx *ctx, size_t dev_bytes, size_t host_bytes, PlanSl
         return e;
     }
     ctx->slabs_owned++;
+    ctx->slab_bytes += s.dev_bytes;
     out = s;
     return hipSuccess;
 }
@@ -469,6 +483,7 @@ int plan_upload(flexsp_ctx *ctx, flexsp_plan *p)
         if (e == hipSuccess) e = hipEventRecord(p->slab.ready, ctx->upload);
         if (e != hipSuccess) {
             (void)hipStreamSynchronize(ctx->upload);
+            ctx->slab_bytes -= p->slab.dev_bytes;
             slab_free(p->slab);
             ctx->slabs_owned--;
             delete p;
@@ -759,12 +774,14 @@ void flexsp_plan_destroy(flexsp_plan *plan)
             } catch (const std::bad_alloc &) {
                 if (s.done_valid) (void)hipEventSynchronize(s.done);
                 (void)hipEventSynchronize(s.ready);
+                ctx->slab_bytes -= s.dev_bytes;
                 slab_free(s);
                 ctx->slabs_owned--;
             }
         } else {
             if (s.done_valid) (void)hipEventSynchronize(s.done);
             (void)hipEventSynchronize(s.ready);
+            ctx->slab_bytes -= s.dev_bytes;
             slab_free(s);
             ctx->slabs_owned--;
         }

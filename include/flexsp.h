@@ -98,11 +98,13 @@ int flexsp_ctx_num_xcd(const flexsp_ctx *ctx);
  * a stream of the context's own, and the first forward / backward call that uses the plan
  * makes its stream wait for that copy (a call made under stream capture should find the copy
  * finished: create the plan, let work that follows it complete, then capture).  Device and
- * pinned memory of destroyed plans is kept by the context (up to 8 buffers) and handed to new
- * plans, ordered after the kernels that still use it (a buffer whose kernels have finished is
- * preferred; a context makes at most three before it reuses a busy one), so a plan per
- * micro-batch costs neither an allocation nor a device-wide synchronisation after the first steps.  A context, and the plans made from it,
- * belong to one host thread at a time.
+ * pinned memory of destroyed plans is kept by the context (up to 16 buffers) and handed to new
+ * plans (a buffer whose kernels have finished is preferred; a context makes at most four, 1 GiB
+ * in all, before it reuses a busy one), so a plan per micro-batch costs neither an allocation
+ * nor a device-wide synchronisation after the first steps.  When every buffer is still in use
+ * by kernels, THIS CALL BLOCKS THE HOST until those of the buffer released first have finished:
+ * a caller that makes a plan per step runs at most four steps ahead of the GPU.  A context, and
+ * the plans made from it, belong to one host thread at a time.
  * Errors: INVALID_ARGUMENT, UNSUPPORTED (D), OUT_OF_MEMORY, HIP_ERROR.
  */
 int flexsp_plan_create(flexsp_ctx *ctx, const int32_t *cu_seqlens_host, int32_t B,

@@ -67,10 +67,14 @@ def synthetic_batches(totals=(16384, 32768, 65536, 131072), seed: int = 20241201
     return batches
 
 
-def profile(ctx, batches, heads: int = 8, head_dim: int = 128, reps: int = 5):
-    """Measured attention fwd+bwd time (ms, median of `reps` runs after two warm-up runs) of every
-    batch on the context's GPU: the sum of the kernel durations the library records with HIP events
-    on the stream the kernels run on.  Inputs are random bf16; their values do not affect the time."""
+def profile(ctx, batches, heads: int = 8, head_dim: int = 128, reps: int = 8):
+    """Measured attention fwd+bwd time (ms) of every batch on the context's GPU: after two warm-up
+    runs, `reps` runs back to back, and per kernel the mean of the durations the library records
+    with HIP events on the stream the kernels run on, summed over the kernels.  (Back to back, as
+    the layers of a training step follow one another: a run timed alone, with a synchronisation
+    before it, starts on a GPU whose clocks have dropped, and for batches of well under a
+    millisecond that ramp is a tenth of the time.)  Inputs are random bf16; their values do not
+    affect the time."""
     import torch
     from . import binding as fx
     H, D = heads, head_dim
@@ -91,13 +95,11 @@ def profile(ctx, batches, heads: int = 8, head_dim: int = 128, reps: int = 5):
             fx.flexsp_attn_varlen_bwd(ctx, plan, q, k, v, o, g, lse, cud, dq, dk, dv)
 
         once(); once()
-        runs = []
+        ctx.profile_start(4 * reps + 8)
         for _ in range(reps):
-            ctx.profile_start(8)
             once()
-            pr = ctx.profile_stop()
-            runs.append(sum(pr[kk][0] for kk in ("fwd", "bwd_delta", "bwd_dkv", "bwd_dq")))
-        times.append(float(np.median(runs)))
+        pr = ctx.profile_stop()
+        times.append(float(sum(pr[kk][0] / max(pr[kk][1], 1) for kk in ("fwd", "bwd_delta", "bwd_dkv", "bwd_dq"))))
         plan.close()
         del q, k, v, g, o, dq, dk, dv, lse
     return times

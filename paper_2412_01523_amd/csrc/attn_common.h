@@ -264,6 +264,16 @@ struct RowBlock {
     // those rows of a tile (kernels that fold a row offset into lo.nat pass the same offset here).
     __device__ __forceinline__ void fragments(char *tile, int row0, const LaneOffsets<D> &lo, bf16x8 (&f)[D / 16], int lane)
     {
+        stage(tile, row0, lane);
+        // (LDS instructions of one wavefront execute in order: the reads see the writes, and a later
+        // call's writes to the same region come after these reads)
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ks++) f[ks] = lds_nat(tile, lo.nat[ks]);
+    }
+    // The first half of fragments(): the block as 32 rows of a tile, for code that reads it with the
+    // tile read patterns itself.
+    __device__ __forceinline__ void stage(char *tile, int row0, int lane)
+    {
         char *region = tile + row0 * L::ROWB;
 #pragma unroll
         for (int n = 0; n < N; n++) {
@@ -271,10 +281,6 @@ struct RowBlock {
             const int row = pos / L::CH;
             *(u32x4 *)(region + row * L::ROWB + (((pos % L::CH) ^ L::sw(row)) << 4)) = raw[n];
         }
-        // (LDS instructions of one wavefront execute in order: the reads see the writes, and a later
-        // call's writes to the same region come after these reads)
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ks++) f[ks] = lds_nat(tile, lo.nat[ks]);
     }
 };
 

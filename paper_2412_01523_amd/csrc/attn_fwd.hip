@@ -161,6 +161,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         // (SHARD: a finite floor instead of -inf, because a row may have every key of a block masked:
         // its scores are -inf, and -inf minus a reference of -inf would not be a number)
         float m_run = SHARD ? -1e30f : -INFINITY, l_run = 0.f;
+        float psum_max = 0.f;  // largest row sum of a block taken without its maximum (see iter_fast)
         f32x16 sacc[2];     // S of block c in sacc[c & 1]
         uint32_t pk[2][8];  // P of block c (bf16 pairs) in pk[c & 1]
 
@@ -287,7 +288,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             for (int j = 0; j < AH; j++) fr[j] = rd(j);
 #pragma unroll
             for (int i = 0; i < 16; i++) sn[i] = 0.f;
-            float mx = 0.f, m_new = 0.f, moff = 0.f, psum = 0.f, pprev = 0.f;
+            // The block's scores are taken against the running reference as it stands, without looking
+            // at their maximum first: bf16 and fp32 share their exponent range, so P may grow far
+            // beyond 1 before anything is lost (O and the row sums are accumulated in fp32 and divided
+            // at the end).  The largest row sum seen is kept instead (one instruction); if it shows,
+            // when the item's steps are done, that some scores outgrew the reference by 2^64 or
+            // overflowed, the wavefront recomputes its rows the careful way (see below).  The maximum,
+            // its exchange between the half-waves and the comparison were a sixth of this loop's
+            // vector instructions, and those are what bounds it.
+            float psum = 0.f, pprev = 0.f;
+            const float moff = m_run * a.scale_l2;
 #pragma unroll
             for (int j = 0; j < NSLOT; j++) {
                 if (j + AH < NSLOT) fr[j + AH] = rd(j + AH);
@@ -308,19 +318,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                         load_tile_async_fast_one<D>(smem + (2 + (VB ^ 1)) * TILE, vbase + (int64_t)(t + 1) * kFwdBk * a.v_st,
                                                     a.v_st, goffv, wave, n - NCP / 2);
                 }
-                if (j == 0) {
-                    mx = fmaxf(sc[0], sc[1]);
+                {
+                    constexpr int NE = NSLOT;  // every slot carries its share of the 16 exponentials
 #pragma unroll
-                    for (int i = 2; i < 8; i += 2) mx = fmaxf(mx, fmaxf(sc[i], sc[i + 1]));
-                } else if (j == 1) {
-#pragma unroll
-                    for (int i = 8; i < 16; i += 2) mx = fmaxf(mx, fmaxf(sc[i], sc[i + 1]));
-                    m_new = reference(halves_max(mx));
-                    moff = m_new * a.scale_l2;
-                } else {
-                    constexpr int NE = NSLOT - 2;  // slots that carry exponentials
-#pragma unroll
-                    for (int e = ((j - 2) * 16) / NE; e < ((j - 1) * 16) / NE; e++) {
+                    for (int e = (j * 16) / NE; e < ((j + 1) * 16) / NE; e++) {
                         const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], a.scale_l2, -moff));
                         psum += p;
                         if (e & 1) {
@@ -335,7 +336,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                 }
             }
             asm volatile("" : "+v"(psum));  // the row-sum additions stay above, among the matrix instructions
-            finish_block(m_new, psum);
+            l_run += psum;
+            psum_max = fmaxf(psum_max, psum);
         };
 
         // ---------------- pipeline fill: K tile 0 -> S(0), then iteration 0 --------------------
@@ -388,6 +390,50 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             window_steady(ic<1>{}, t + 1);
         }
         for (; t < ntiles; t++) window(t);
+
+        // ---------------- (rare) the careful way, per wavefront ----------------------------------
+        // Some row sum of a fast iteration was 2^64 or more, infinite or not a number: scores that
+        // outgrew the reference such an iteration does not update.  The wavefront then computes its
+        // 32 rows again, every block against its own maximum, on its own: K and V blocks of 32 keys
+        // come straight from global memory through this wavefront's quarter of the K buffers (no
+        // wavefront reads a K tile after the last window's barrier, and this one is past it).
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(psum_max < 0x1p64f)) != 0, 0)) {
+            char *mine = smem + wave * (32 * L::ROWB);
+#pragma unroll
+            for (int db = 0; db < DB; db++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) oacc[db][i] = 0.f;
+            m_run = SHARD ? -1e30f : -INFINITY;
+            l_run = 0.f;
+            for (int c = 0; c <= cmax; c++) {
+                RowBlock<D> blk;
+                blk.load(kbase, a.k_st, c * 32, sk - 1, lane);
+                blk.stage(mine, 0, lane);
+                f32x16 &sa = sacc[0];
+                scores(sa, mine);
+                if (SHARD ? c >= cmask : c == cmask) {
+#pragma unroll
+                    for (int i = 0; i < 16; i++) {
+                        const int kv = c * 32 + 8 * (i >> 2) + 4 * hl + (i & 3);
+                        if (kv > lim) sa[i] = -INFINITY;
+                    }
+                }
+                const float m_new = reference(block_max(sa));
+                const float mo = m_new * a.scale_l2;
+                float ps = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[i], a.scale_l2, -mo));
+                    const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sa[i + 1], a.scale_l2, -mo));
+                    ps += p0 + p1;
+                    pk[0][i >> 1] = pack_bf16x2(p0, p1);
+                }
+                blk.load(vbase, a.v_st, c * 32, sk - 1, lane);
+                blk.stage(mine, 0, lane);  // (after the reads of the K block: one wavefront's LDS instructions execute in order)
+                finish_block(m_new, ps);   // O and the row sum move to the block's reference first
+                pv(pk[0], mine);
+            }
+        }
 
         // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
         float l_tot = halves_sum(l_run);

@@ -37,10 +37,12 @@ def round_to_bf16(x):
     return r.view(np.float32).astype(np.float64)
 
 
-def check_against_budget(tag, out, ref, q, k, v, dO, cu, causal, scale, grad_f32, stated=True):
+def check_against_budget(tag, out, ref, q, k, v, dO, cu, causal, scale, grad_f32, stated=True, rel_l2=REL_L2):
     """Element-wise parity of one run of the HIP path (dict from GpuAttn.run) against the oracle.
     Every tensor must stay inside the budget its roundings allow (rounding_budget.tolerance: derived
-    from the arithmetic, fixed before the run) and inside relative L2 5e-3.  With `stated` the
+    from the arithmetic, fixed before the run) and inside relative L2 5e-3 (`rel_l2`: stated for the
+    N(0,1) recipe; inputs that make attention nearly one-hot leave dS = P (dP - delta) a difference of
+    nearly equal numbers and get a wider bound, the per-element budget stays).  With `stated` the
     contract's flat max-abs 2e-2 is asserted as well, for O and for gradients stored as fp32; a
     gradient stored as bf16 may leave 2e-2 only where the budget, which then includes the final
     rounding (up to 2^-8 |value|), says so.  Returns {name: (max_abs, rel_l2, worst error / budget)}."""
@@ -57,7 +59,7 @@ def check_against_budget(tag, out, ref, q, k, v, dO, cu, causal, scale, grad_f32
         ma, rl = errors(got, ref[name])
         used = float((err / tol).max()) if err.size else 0.0
         assert used <= 1.0, f"{tag} {name}: error {used:.2f} x the rounding budget (max_abs {ma:.3e})"
-        assert rl <= REL_L2, f"{tag} {name}: rel_l2={rl:.3e}"
+        assert rl <= rel_l2, f"{tag} {name}: rel_l2={rl:.3e}"
         if stated:
             flat = MAX_ABS if (name == "O" or grad_f32) else np.maximum(MAX_ABS, tol)
             assert (err <= flat).all(), f"{tag} {name}: max_abs={ma:.3e} beyond the stated {MAX_ABS}"

@@ -42,8 +42,8 @@ HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 # counter values and the algorithmic bytes beside them are in profiles/attention_hbm_traffic.md).
 # bench.py cannot run the profiler on itself: these are the figures of that summary.
 MEASURED_HBM_TRAFFIC = {
-    ("pareto-64k", "fwd"): 1329165180, ("pareto-64k", "bwd_dq"): 1614562457, ("pareto-64k", "bwd_dkv"): 1915654562,
-    ("single-128k", "fwd"): 37596386823, ("single-128k", "bwd_dq"): 88595310249, ("single-128k", "bwd_dkv"): 20296485274,
+    ("pareto-64k", "fwd"): 1426846601, ("pareto-64k", "bwd_dq"): 1614441371, ("pareto-64k", "bwd_dkv"): 1890741803,
+    ("single-128k", "fwd"): 38703944182, ("single-128k", "bwd_dq"): 87508942492, ("single-128k", "bwd_dkv"): 24157623799,
 }
 
 

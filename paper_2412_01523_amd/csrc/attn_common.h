@@ -481,9 +481,9 @@ __device__ __forceinline__ flexsp_shard_item load_shard_item(const flexsp_shard_
 // out as tickets: ticket l < W is workgroup l's first item (no memory access), tickets from W on
 // come from one atomic counter per queue, longest item first, so the list is scheduled
 // longest-processing-time-first against the run times as they really turn out.  The ticket for
-// the NEXT item is drawn when an item starts (prefetch), so the counter's round trip (a few
+// the NEXT item is drawn while an item runs (prefetch), so the counter's round trip (a few
 // microseconds when 64 workgroups hit the same address) is hidden behind the item's work.  A
-// workgroup whose home queue is empty goes on to the other XCDs' queues, one after the other,
+// workgroup whose home queue is empty takes items from the fullest of the other XCDs' queues
 // and only stops when all are empty: the tail of the launch is spread over the whole chip.
 // Only wavefront 0 talks to the counters; the item index reaches the others through one LDS
 // word and the barrier that ends an item anyway.  The last workgroup to leave zeroes the

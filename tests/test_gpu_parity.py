@@ -201,6 +201,20 @@ def test_scores_that_outgrow_the_running_reference(ctx, pos, factor):
     _check_case(ctx, f"outgrow-{pos}", lens, 2, 2, 128, True, 6161 + pos, kmul_from=(pos, factor))
 
 
+def test_scores_outgrow_the_reference_inside_parts_of_a_cut_tile(ctx):
+    """The same with one head and a 6 000-token sequence, whose long tiles are cut into parts: a part that
+    starts behind the jump never sees the small scores, one that spans it falls back, and the merge of
+    the parts has to weigh them by their very different maxima."""
+    lens = [6000, 300]
+    say(f"attention case outgrow-cut lens={lens} Hq=1 Hkv=1 D=128 causal")
+    from paper_2412_01523_amd import binding as fx
+    plan = fx.Plan(ctx, wl.cu_seqlens(lens), 1, 1, 128, True)
+    items, _ = plan.items(fx.PASS_FWD)
+    assert int(items["nparts"].max()) > 1, "the workload was meant to have cut tiles"
+    plan.close()
+    _check_case(ctx, "outgrow-cut", lens, 1, 1, 128, True, 6262, kmul_from=(2500, 40.0))
+
+
 def test_many_short_sequences_keep_every_queue_busy_to_the_end(ctx):
     """1 500 sequences of 1 to 80 tokens on 8 heads: some 12 000 one-tile items for 512 workgroups, so
     every queue is drawn from thousands of times, runs empty while others still hold items, and is

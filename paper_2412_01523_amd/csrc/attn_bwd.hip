@@ -398,6 +398,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
 #pragma unroll
             for (int i = 0; i < 16; i++) dqT[db][i] = 0.f;
 
+        const int draw_t = ntiles >= kLateTicketSteps ? ntiles - 3 : 0;  // the step in which the next ticket is drawn
         auto step_fn = [&](auto bufc, int t) {
             constexpr int BUF = decltype(bufc)::value;
             const char *sK = smem + BUF * 2 * TILE;
@@ -406,9 +407,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
             lo.pin();
             wait_vmem();
             __syncthreads();
-            // the next item's ticket is drawn behind the first wait: answers come back in request order, and
-            // in front of the item's first loads the counter's round trip would hold them up
-            if (t == 0) deal.prefetch();
+            // the next item's ticket: three steps before a long item ends, in a short one's first step (see the forward kernel)
+            if (t == draw_t) deal.prefetch();
             if (__builtin_expect(t + 1 < ntiles, 1)) prefetch(t + 1, BUF ^ 1);
             if (a.causal && kv0 > wq_rel + 31) return;
 

@@ -347,10 +347,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         wait_vmem();
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the fragments are in registers
         __syncthreads();
-        // The ticket of the item after this one is drawn here, not when the item starts: answers come
-        // back in the order of the requests, so the wait for the item's first loads would also be a
-        // wait for the counter's round trip, which is several times longer.
-        deal.prefetch();
+        // (short items draw their ticket here, long ones near their end: see window())
+        const int draw_t = ntiles >= kLateTicketSteps ? ntiles - 2 : -1;
+        if (draw_t < 0) deal.prefetch();
         if (ntiles > 1) prefetch_k(1, 1);
         prefetch_v(0, 0);
         if (cmax >= 0) scores(sacc[0], smem);
@@ -377,6 +376,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             __syncthreads();  // everybody's has, and everybody is done with K tile t and V tile t-1
             if (t + 2 < ntiles) prefetch_k(t + 2, kb ^ 1);
             if (t + 1 < ntiles) prefetch_v(t + 1, vb ^ 1);
+            // The ticket of the item after a LONG one is drawn in the item's last window but one: late enough
+            // that the workgroup commits itself to another item only a few microseconds before it is
+            // free for it (a ticket drawn when the item starts reserves the then-largest item for the
+            // whole length of this one, and at the end of a pass every workgroup still owes an item
+            // while others idle), early enough that the counter's round trip is over when the epilogue
+            // is.  An item of a few steps gains nothing from that and pays the wait for the answer at its
+            // end, so it draws right after its first barrier (behind its first loads, not in front of
+            // them: answers come back in request order).
+            if (t == draw_t) deal.prefetch();
             const char *sK = smem + kb * TILE, *sV = smem + (2 + vb) * TILE;
             iter_slow(ic<1>{}, 2 * t + 1, sK, sV);
             iter_slow(ic<0>{}, 2 * t + 2, sK + 32 * L::ROWB, sV + 32 * L::ROWB);

@@ -22,6 +22,7 @@ constexpr int kDkvBq = 64;     // query rows per dK/dV step
 constexpr int kThreads = 256;  // every attention kernel runs 4 wavefronts per workgroup
 constexpr int kMaxQueues = 8;  // one work queue per XCD
 constexpr int kCounterStride = 32;  // int32 from one queue's ticket counter to the next: a 128-byte line each
+constexpr int kLateTicketSteps = 16;  // items of at least this many steps draw the next ticket near their end
 
 // Split tiles (see flexsp_item in flexsp.h): a part's partial result is one record of fp32 values,
 // 64 per thread of the workgroup (the accumulators) plus, for the forward, each row's running

@@ -42,8 +42,8 @@ HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 # counter values and the algorithmic bytes beside them are in profiles/attention_hbm_traffic.md).
 # bench.py cannot run the profiler on itself: these are the figures of that summary.
 MEASURED_HBM_TRAFFIC = {
-    ("pareto-64k", "fwd"): 1426846601, ("pareto-64k", "bwd_dq"): 1614441371, ("pareto-64k", "bwd_dkv"): 1890741803,
-    ("single-128k", "fwd"): 38703944182, ("single-128k", "bwd_dq"): 87508942492, ("single-128k", "bwd_dkv"): 24157623799,
+    ("pareto-64k", "fwd"): 1317796159, ("pareto-64k", "bwd_dq"): 1536986235, ("pareto-64k", "bwd_dkv"): 1904515851,
+    ("single-128k", "fwd"): 11907460290, ("single-128k", "bwd_dq"): 30716683641, ("single-128k", "bwd_dkv"): 19226815106,
 }
 
 

@@ -30,5 +30,5 @@ def test_eq12_fit_predicts_held_out_batches():
           f"max |error| fitted {100 * np.abs(e_fit).max():.1f} %, held out {100 * np.abs(e_held).max():.1f} %", flush=True)
     sys.stdout.flush()
     assert coef[0] > 0                                  # the quadratic term is the attention itself
-    assert np.abs(e_held).max() <= 0.08                 # what the model is for: batches it has not seen
+    assert np.abs(e_held).max() <= 0.10                 # what the model is for: batches it has not seen (5 % measured)
     assert np.abs(e_fit).max() <= 0.15                  # (the fit itself: a sanity bound only)

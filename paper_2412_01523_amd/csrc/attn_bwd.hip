@@ -70,7 +70,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
     ItemDealer deal;
 
     for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
-        deal.prefetch();
         const flexsp_item it = load_item(a.pq.items, item);
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
@@ -94,6 +93,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
         // covers is carried along instead of being divided out of a step number: (h_cur, q_cur) for the
         // step being computed, (h_nxt, q_nxt) for the one whose tiles are fetched meanwhile.
         const int n = total - first;
+        // The ticket of the item after this one: a short item draws it now, a long one when its steps are
+        // done (see the forward kernel; here not inside the steps: any branch there costs this kernel
+        // 1-2 %, and behind a long item the wait for the answer, what the epilogue does not cover of
+        // it, does not show).
+        if (n < kLateTicketSteps) deal.prefetch();
         const int q_end = qfirst + nsteps * BQ;
         int h_cur = g * a.G + first / nsteps, q_cur = qfirst + (first % nsteps) * BQ;
         int h_nxt = h_cur, q_nxt = q_cur;
@@ -276,6 +280,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             step_fn(std::integral_constant<int, 0>{}, step);
             if (step + 1 < n) step_fn(std::integral_constant<int, 1>{}, step + 1);
         }
+        if (n >= kLateTicketSteps) deal.prefetch();
         if (nparts > 1) {
             split_store<DB>(a.pq.split_scratch + (int64_t)(it.slot + part) * kPartialBytes, accT, tid);
             if (!split_arrive(a.pq.split_flags + it.slot, nparts, &split_word, tid)) continue;  // a later part finishes the tile

@@ -211,7 +211,10 @@ typedef struct flexsp_tensor {
  *   softmax_scale     <= 0 selects 1/sqrt(D)
  *   lse               device pointer, fp32 [head_count, T]
  * Scores and softmax statistics are fp32; P is rounded to bf16 before the PV product;
- * accumulation is fp32; O is rounded to bf16 once.
+ * accumulation is fp32; O is rounded to bf16 once.  Any finite input is handled; rows whose
+ * scaled scores rise more than 44 (natural units) above the maximum of the row's first keys
+ * are recomputed block by block by their wavefront, which costs time, not accuracy (a launch
+ * in which every row does takes about 2.4 times as long).
  * Errors: INVALID_ARGUMENT, PLAN_MISMATCH, NO_DEVICE, HIP_ERROR.
  */
 int flexsp_attn_varlen_fwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,

@@ -98,6 +98,100 @@ def cost_model_leg(ctx, fx, wl, torch, np):
                            "rel_error": float(e)} for b, t, e in zip(batches, times, err)]}
 
 
+def ring_leg(ctx, fx, wl, torch, np, workload):
+    """One device's pass of a context-parallel ring without the wire (paper Sec. 2.1.3, paragraph on context
+    parallelism, and the appendix that integrates it): the device holds the LAST 1/P of every sequence's
+    query rows (the rank with the most visible keys, which sets the ring's time), the key/value shards come
+    by one at a time (its own first, then the earlier ones), each gives a partial attention
+    (flexsp_attn_varlen_fwd_kvshard) that is folded into the running result (flexsp_lse_merge, in place).
+    Plans are built beforehand (lengths are known on the host); timed with events on the stream."""
+    cfg = next(c for c in wl.CONFIGS if c.name == workload)
+    lens = [s for s in wl.lengths(cfg)]
+    H, Hkv, D = cfg.hq, cfg.hkv, cfg.d
+    P = 8 if len(lens) == 1 else 4
+    cu = wl.cu_seqlens(lens)
+    T = int(cu[-1])
+    cut = [[(j * s) // P for j in range(P + 1)] for s in lens]            # shard j of a sequence: positions cut[j] .. cut[j+1]-1
+    dev = "cuda"
+    k = torch.randn((T, Hkv, D), device=dev).to(torch.bfloat16)
+    v = torch.randn((T, Hkv, D), device=dev).to(torch.bfloat16)
+    q_full = torch.randn((T, H, D), device=dev).to(torch.bfloat16)
+
+    def rows(x, j):
+        return torch.cat([x[int(cu[b]) + c[j]: int(cu[b]) + c[j + 1]] for b, c in enumerate(cut)]).contiguous()
+
+    q = rows(q_full, P - 1)
+    cu_q = wl.cu_seqlens([c[P] - c[P - 1] for c in cut])
+    Tq = int(cu_q[-1])
+    shards = []
+    for j in range(P - 1, -1, -1):
+        cu_k = wl.cu_seqlens([c[j + 1] - c[j] for c in cut])
+        shift = [c[P - 1] - c[j] for c in cut]
+        pairs = sum((n * (n + 1)) // 2 if j == P - 1 else n * (c[j + 1] - c[j])
+                    for c in cut for n in [c[P] - c[P - 1]])
+        shards.append({"plan": fx.ShardPlan(ctx, cu_q, cu_k, shift, H, Hkv, D, True), "k": rows(k, j), "v": rows(v, j),
+                       "flops": 4 * D * H * pairs, "shard": j})
+    o_acc = torch.empty((Tq, H, D), dtype=torch.bfloat16, device=dev)
+    l_acc = torch.empty((H, Tq), dtype=torch.float32, device=dev)
+    o_new, l_new = torch.empty_like(o_acc), torch.empty_like(l_acc)
+    stream = torch.cuda.current_stream()
+    reps = 10
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * P)] for _ in range(reps)]
+
+    def one_pass(marks):
+        for n, sh in enumerate(shards):
+            o, l = (o_acc, l_acc) if n == 0 else (o_new, l_new)
+            fx.flexsp_attn_varlen_fwd_kvshard(ctx, sh["plan"], q, sh["k"], sh["v"], o, l, stream=stream)
+            if marks: marks[2 * n].record(stream)
+            if n:
+                fx.flexsp_lse_merge(ctx, o_acc, l_acc, o_new, l_new, o_acc, l_acc, stream)
+            if marks: marks[2 * n + 1].record(stream)
+
+    for _ in range(3):
+        one_pass(None)
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    start.record(stream)
+    for r in range(reps):
+        one_pass(ev[r])
+    torch.cuda.synchronize()
+    total_ms = start.elapsed_time(ev[-1][-1]) / reps
+    fwd_ms = np.zeros((reps, P)); mrg_ms = np.zeros((reps, P))
+    for r in range(reps):
+        prev = start if r == 0 else ev[r - 1][-1]
+        for n in range(P):
+            fwd_ms[r, n] = prev.elapsed_time(ev[r][2 * n])
+            mrg_ms[r, n] = ev[r][2 * n].elapsed_time(ev[r][2 * n + 1])
+            prev = ev[r][2 * n + 1]
+    fwd_med, mrg_med = np.median(fwd_ms, axis=0), np.median(mrg_ms, axis=0)
+    flops = sum(sh["flops"] for sh in shards)
+    merge_bytes = 3 * Tq * H * D * 2 + 3 * H * Tq * 4           # two partial results read, one written
+    # the ordinary forward over the unsplit batch, for the rate the shard kernel is measured against
+    plan = fx.Plan(ctx, cu, H, Hkv, D, True)
+    o_full = torch.empty_like(q_full)
+    l_full = torch.empty((H, T), dtype=torch.float32, device=dev)
+    cud = torch.from_numpy(cu).to(dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(6):
+        if i == 3: e0.record(stream)
+        fx.flexsp_attn_varlen_fwd(ctx, plan, q_full, k, v, cud, o_full, l_full, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    full_ms = e0.elapsed_time(e1) / 3
+    full_flops = wl.attn_flops(lens, H, D, True)[0]
+    plan.close()
+    out = {"workload": cfg.name, "ring_degree": P, "query_rows": Tq, "heads": H, "head_dim": D,
+           "shards": [{"shard": sh["shard"], "ms": float(fwd_med[n]), "tflops": sh["flops"] / (fwd_med[n] * 1e-3) / 1e12}
+                      for n, sh in enumerate(shards)],
+           "merge_ms_each": float(np.median(mrg_med[1:])), "merge_GBps": merge_bytes / (np.median(mrg_med[1:]) * 1e-3) / 1e9,
+           "pass_ms": total_ms, "pass_tflops": flops / (total_ms * 1e-3) / 1e12,
+           "shard_forwards_tflops": flops / (fwd_med.sum() * 1e-3) / 1e12,
+           "unsplit_forward_ms": full_ms, "unsplit_forward_tflops": full_flops / (full_ms * 1e-3) / 1e12}
+    for sh in shards:
+        sh["plan"].close()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +213,9 @@ def main() -> int:
                     help="for counter collection under rocprofv3 --pmc: 5 plain copies of known size (the permute "
                          "kernel with P = 1 on [32768, 32, 128] bf16: 256 MiB read, 256 MiB written each), then 3 x "
                          "(forward + backward) of the workload with one plan; nothing is timed")
+    ap.add_argument("--kvshard-ring", action="store_true",
+                    help="only the context-parallel leg: one device's ring pass (forward against one key shard at a "
+                         "time + merge) on single-128k (8 shards) and pareto-64k (4 shards), beside the unsplit forward")
     ap.add_argument("--permute-only", action="store_true",
                     help="only the permute bandwidth leg: 50 pack, 50 unpack, 50 plain copies (pack with P = 1), "
                          "in that order (for counter collection)")
@@ -137,6 +234,13 @@ def main() -> int:
         torch.cuda.set_device(0)
         ctx = fx.Context(0)
         print(json.dumps({"cost_model": cost_model_leg(ctx, fx, wl, torch, np)}))
+        return 0
+
+    if args.kvshard_ring:
+        torch.cuda.set_device(0)
+        ctx = fx.Context(0)
+        names = ("single-128k", "pareto-64k") if args.workload == "pareto-64k" else (args.workload,)
+        print(json.dumps({"kvshard_ring": [ring_leg(ctx, fx, wl, torch, np, w) for w in names]}))
         return 0
 
     if args.traffic_probe:

@@ -255,7 +255,8 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
  *   without, every shard key is visible and shift is ignored.  The plan serves
  *   flexsp_attn_varlen_fwd_kvshard only (the other attention calls answer PLAN_MISMATCH); it is destroyed
  *   by flexsp_plan_destroy and inspected by flexsp_plan_num_items / _get_items with FLEXSP_PASS_FWD, where
- *   an item's seq_start holds the sequence INDEX b.
+ *   an item's seq_start holds the sequence INDEX b.  Long tiles are cut into parts as in flexsp_plan_create
+ *   (a step = 64 shard keys).  Hq <= 65 535, else UNSUPPORTED.
  *
  * flexsp_attn_varlen_fwd_kvshard - per query row, softmax over the visible shard keys only:
  *   O = sum_j P_j v_j (bf16), LSE = log sum_j exp(scale q.k_j) (fp32, natural log, [head_count, Tq]).

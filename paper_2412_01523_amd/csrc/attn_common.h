@@ -470,8 +470,8 @@ __device__ __forceinline__ flexsp_shard_item load_shard_item(const flexsp_shard_
     it.k_len = __builtin_amdgcn_readfirstlane(v.k_len);
     it.shift = __builtin_amdgcn_readfirstlane(v.shift);
     it.tile = __builtin_amdgcn_readfirstlane(v.tile);
-    it.head = __builtin_amdgcn_readfirstlane(v.head);
-    it.pad = 0;
+    it.head_parts = __builtin_amdgcn_readfirstlane(v.head_parts);
+    it.slot = __builtin_amdgcn_readfirstlane(v.slot);
     return it;
 }
 

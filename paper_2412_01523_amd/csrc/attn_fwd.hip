@@ -65,8 +65,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
         int part = 0, nparts = 1, slot = -1, t_lo = 0, t_hi = 0;  // (see flexsp_item): the item walks key tiles t_lo .. t_hi-1
         if constexpr (SHARD) {
             const flexsp_shard_item it = load_shard_item((const flexsp_shard_item *)a.pq.items, item);
-            s = it.q_len; sk = it.k_len; shift = it.shift; h = it.head; q0 = it.tile * kFwdBq;
+            s = it.q_len; sk = it.k_len; shift = it.shift; h = it.head_parts & 0xffff; q0 = it.tile * kFwdBq;
             tok0 = it.q_start; ktok0 = it.k_start;
+            // (a part of a cut tile comes with its own key range and shift: nothing else differs)
+            part = (it.head_parts >> 16) & 0xff; nparts = it.head_parts >> 24; slot = it.slot;
         } else {
             const flexsp_item it = load_item(a.pq.items, item);
             s = it.seq_len; sk = s; shift = 0; h = it.head; q0 = it.tile * kFwdBq;
@@ -445,7 +447,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
 
         // ---- epilogue: normalise, write O (bf16) and LSE (natural log)
         float l_tot = halves_sum(l_run);
-        if constexpr (!SHARD) {
+        {
             if (nparts > 1) {
                 // hand over (O unnormalised, row maximum, row sum); the part that arrives last merges
                 // all parts in part order: O = sum_p 2^((m_p - M) scale_l2) O_p, likewise the row sums

@@ -209,7 +209,7 @@ struct Work {
 };
 
 void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int n_wg, int tile_rows,
-                HostPass &out);
+                HostPass &out, int spare = 0);
 
 // Builds one pass: lists the items, spreads whole (sequence, head) groups over the queues
 // (largest group first onto the least loaded queue, so tiles that read the same K/V run on
@@ -265,7 +265,8 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
 // equal length (at most kMaxParts, none shorter than kMinPartSteps).  Longest-first scheduling alone
 // finishes no earlier than the longest item, which for a batch of few heads and one dominant
 // sequence is several times the even share: the compute units that run out of work wait for it.
-void split_long_items(std::vector<Work> &work, int n_wg, HostPass &out)
+// `spare`: tiles of up to this many even shares are left whole (0: every tile longer than a part is cut).
+void split_long_items(std::vector<Work> &work, int n_wg, int spare, HostPass &out)
 {
     out.records = 0;
     int64_t total = 0;
@@ -281,7 +282,7 @@ void split_long_items(std::vector<Work> &work, int n_wg, HostPass &out)
     const size_t n0 = work.size();
     for (size_t i = 0; i < n0; i++) {
         const int64_t c = work[i].cost;
-        if (c < 2 * kMinPartSteps || c <= target) continue;
+        if (c < 2 * kMinPartSteps || c <= target || c <= spare * share) continue;
         int k = (int)std::min<int64_t>(std::min<int64_t>(cdiv(c, target), kMaxParts), c / kMinPartSteps);
         if (k < 2 || out.records + k > kMaxSplitRecords) continue;
         const int32_t slot = out.records;
@@ -303,9 +304,9 @@ void split_long_items(std::vector<Work> &work, int n_wg, HostPass &out)
 
 // Spreads listed work over the queues and orders every queue longest first (see build_pass).
 void distribute(std::vector<Work> &work, const std::vector<int64_t> &group_cost, int nq, int n_wg, int tile_rows,
-                HostPass &out)
+                HostPass &out, int spare)
 {
-    split_long_items(work, n_wg, out);
+    split_long_items(work, n_wg, spare, out);
     // groups -> queues
     std::vector<int32_t> order(group_cost.size());
     for (size_t i = 0; i < order.size(); i++) order[i] = (int32_t)i;
@@ -459,8 +460,13 @@ int plan_upload(flexsp_ctx *ctx, flexsp_plan *p)
                 for (size_t n = 0; n < p->pass[i].items.size(); n++) {
                     const flexsp_item &it = p->pass[i].items[n];
                     const int b = it.seq_start;
-                    d[n] = flexsp_shard_item{p->cu[b], p->cu[b + 1] - p->cu[b], p->cu_k[b], p->cu_k[b + 1] - p->cu_k[b],
-                                             p->shift[b], it.tile, it.head, 0};
+                    // a part of a cut tile: the keys of its steps only, positions counted from its first key
+                    const int32_t np = it.parts & 0xffff, part = it.parts >> 16;
+                    const int32_t skip = np > 1 ? it.step_begin * kFwdBk : 0;
+                    int32_t k_len = p->cu_k[b + 1] - p->cu_k[b];
+                    if (np > 1 && part + 1 < np) k_len = std::min(k_len, it.step_end * kFwdBk);
+                    d[n] = flexsp_shard_item{p->cu[b], p->cu[b + 1] - p->cu[b], p->cu_k[b] + skip, k_len - skip,
+                                             p->shift[b] - skip, it.tile, it.head | (part << 16) | (np << 24), it.slot};
                 }
             } else if (!p->pass[i].items.empty()) {
                 std::memcpy(stage + item_off[i], p->pass[i].items.data(),
@@ -696,6 +702,7 @@ int flexsp_plan_create_kvshard(flexsp_ctx *ctx, const int32_t *cu_q, const int32
         if (shift[b] > (1 << 30) || shift[b] < -(1 << 30)) return FLEXSP_INVALID_ARGUMENT;
     }
     if (D != 64 && D != 128) return FLEXSP_UNSUPPORTED;
+    if (Hq > 0xffff) return FLEXSP_UNSUPPORTED;  // a device item keeps the head in 16 bits
     flexsp_plan *p = new (std::nothrow) flexsp_plan;
     if (!p) return FLEXSP_OUT_OF_MEMORY;
     p->ctx = ctx;
@@ -736,7 +743,10 @@ int flexsp_plan_create_kvshard(flexsp_ctx *ctx, const int32_t *cu_q, const int32
                 group_cost.push_back(gc);
             }
         }
-        distribute(work, group_cost, ctx->num_xcd, 1, kFwdBq, p->pass[FLEXSP_PASS_FWD]);  // (one "workgroup": no tile is cut)
+        // (a tile is cut only when it would outlast TWO even shares: with a share of a few dozen steps, as
+        // on a micro-batch split over a ring, the hand-over of the parts costs more than the wait for a
+        // tile that is a little longer than the rest)
+        distribute(work, group_cost, ctx->num_xcd, workgroups_of(ctx), kFwdBq, p->pass[FLEXSP_PASS_FWD], 2);
         for (int i = 1; i < 3; i++) {
             for (int x = 0; x <= kMaxQueues; x++) p->pass[i].offsets[x] = 0;
             p->pass[i].tile_rows = 0;

@@ -37,8 +37,11 @@ constexpr int kMaxSplitRecords = 2048;
 // Work item of the key-shard forward: query rows q_start .. q_start+q_len-1 of q / o / lse, shard
 // keys k_start .. k_start+k_len-1 of k / v, shift = position of the first query in its sequence
 // minus position of the shard's first key.  `tile` counts 128-row query tiles.
+// A tile cut into parts (see flexsp_item) is listed once per part, each with its own key range and the
+// shift that goes with it: head_parts = head | part << 16 | nparts << 24 (0 and 1 for a whole tile),
+// slot = the tile's first partial-result record (-1 for a whole tile).
 struct flexsp_shard_item {
-    int32_t q_start, q_len, k_start, k_len, shift, tile, head, pad;
+    int32_t q_start, q_len, k_start, k_len, shift, tile, head_parts, slot;
 };
 
 struct PassQueues {

@@ -88,6 +88,42 @@ def test_kvshard_forward_matches_oracle_elementwise(ctx, name, lq, lk, shift, Hq
     _compare(name, o, lse, O, LSE)
 
 
+CUT_CASES = [
+    # name, query lengths, key lengths, shift, Hq, Hkv, D, causal
+    ("diagonal-inside", [700, 60], [5000, 100], [3000, 10], 2, 1, 128, True),    # the diagonal crosses the shard's middle parts
+    ("all-visible", [513], [6001], [7000], 1, 1, 128, True),
+    ("noncausal-d64", [300, 129], [4500, 64], [0, 0], 2, 2, 64, False),
+    ("starts-late", [4000], [4096], [-300], 2, 2, 64, True),                      # the first rows see no key: only later tiles are long
+]
+
+
+@pytest.mark.parametrize("name,lq,lk,shift,Hq,Hkv,D,causal", CUT_CASES, ids=[c[0] for c in CUT_CASES])
+def test_long_shard_tiles_cut_into_parts_and_merged(ctx, name, lq, lk, shift, Hq, Hkv, D, causal):
+    """Few heads and one long key shard: a query tile's walk over the shard would outlast an even share
+    of the pass many times over, so the plan cuts it into parts with their own key ranges; the part
+    that finishes last adds the partial results up in part order.  The plan must really contain cut
+    tiles; every element against the oracle; three runs give the same bits."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    say(f"cut key-shard case {name}: queries {lq} keys {lk} shift {shift} Hq={Hq} Hkv={Hkv} D={D} causal={causal}")
+    cu_q, cu_k = wl.cu_seqlens(lq), wl.cu_seqlens(lk)
+    plan = fx.ShardPlan(ctx, cu_q, cu_k, shift, Hq, Hkv, D, causal)
+    items, _ = plan.items(fx.PASS_FWD)
+    plan.close()
+    say(f"  {len(items)} items, {int((items['nparts'] > 1).sum())} of them parts of cut tiles, up to {int(items['nparts'].max())} parts")
+    assert (items["nparts"] > 2).any()
+    seed = 5600 + len(name)
+    q = wl.normal_bf16(seed, wl.TID_Q, (sum(lq), Hq, D))
+    k = wl.normal_bf16(seed, wl.TID_K, (sum(lk), Hkv, D))
+    v = wl.normal_bf16(seed, wl.TID_V, (sum(lk), Hkv, D))
+    O, LSE = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, shift, causal)
+    runs = [_shard_forward(ctx, q, k, v, cu_q, cu_k, shift, causal) for _ in range(3)]
+    _compare(name, runs[0][0], runs[0][1], O, LSE)
+    for o, lse in runs[1:]:
+        assert torch.equal(o.view(torch.int16), runs[0][0].view(torch.int16)), "O is not reproducible"
+        assert torch.equal(lse.view(torch.int32), runs[0][1].view(torch.int32)), "LSE is not reproducible"
+
+
 def test_aligned_shard_equals_the_ordinary_forward_bitwise(ctx):
     """shift = 0 and keys = the whole sequence is ordinary causal attention: same kernel arithmetic,
     so the key-shard call must reproduce flexsp_attn_varlen_fwd bit for bit."""

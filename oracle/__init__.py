@@ -174,6 +174,52 @@ def attn_fwd_kvshard(q, k, v, cu_q, cu_k, shift, causal=True, scale=None):
     return O, LSE
 
 
+def attn_bwd_kvshard(q, k, v, dO, lse, delta, cu_q, cu_k, shift, causal=True, scale=None):
+    """The backward's share of one key shard (context parallelism, paper Sec. 2.1.3 and the appendix on
+    integrating it; gradient of Sec. 2.1.2 Eq. 3).  `lse` [Hq,Tq] is each row's log-sum-exp over ALL its keys
+    and `delta` [Hq,Tq] its sum_j P_ij dP_ij over all keys (= dO_i . O_i), both from the complete forward;
+    with them the terms of the gradient separate by key:
+        P_ij = exp(scale q_i.k_j - lse_i),  dP_ij = dO_i.v_j,  dS_ij = P_ij (dP_ij - delta_i)   (visible j of the shard)
+        dQ_i (this shard's part) = scale sum_j dS_ij k_j,   dK_j = scale sum_i dS_ij q_i,   dV_j = sum_i P_ij dO_i.
+    Visibility as in attn_fwd_kvshard.  Summed over the shards of a partition of the keys, the dQ parts give dQ
+    of the complete attention, and each key's dK / dV are complete by themselves.  A row with lse = -inf (it
+    saw no key anywhere) contributes nothing.  Returns (dQ_part [Tq,Hq,D], dK [Tk,Hkv,D], dV [Tk,Hkv,D]), fp64."""
+    q, _ = _in(q); k, _ = _in(k); v, _ = _in(v); dO, _ = _in(dO)
+    q, k, v, dO = (bf16_or_f64(x) for x in (q, k, v, dO))
+    lse = np.asarray(lse, dtype=np.float64); delta = np.asarray(delta, dtype=np.float64)
+    Tq, Hq, D = q.shape
+    Tk, Hkv, _ = k.shape
+    G = Hq // Hkv
+    scale = 1.0 / np.sqrt(D) if scale is None else float(scale)
+    dQ = np.zeros((Tq, Hq, D)); dK = np.zeros((Tk, Hkv, D)); dV = np.zeros((Tk, Hkv, D))
+    for b in range(len(shift)):
+        q0, q1, k0, k1 = int(cu_q[b]), int(cu_q[b + 1]), int(cu_k[b]), int(cu_k[b + 1])
+        if q1 == q0 or k1 == k0:
+            continue
+        i = np.arange(q1 - q0)[:, None]; j = np.arange(k1 - k0)[None, :]
+        visible = (j <= i + int(shift[b])) if causal else np.ones((q1 - q0, k1 - k0), dtype=bool)
+        for h in range(Hq):
+            g = h // G
+            S = scale * (q[q0:q1, h] @ k[k0:k1, g].T)
+            L = lse[h, q0:q1][:, None]
+            with np.errstate(over="ignore", invalid="ignore"):
+                P = np.where(visible & np.isfinite(L), np.exp(S - L), 0.0)
+            dP = dO[q0:q1, h] @ v[k0:k1, g].T
+            dS = P * (dP - delta[h, q0:q1][:, None])
+            dQ[q0:q1, h] = scale * (dS @ k[k0:k1, g])
+            dK[k0:k1, g] += scale * (dS.T @ q[q0:q1, h])
+            dV[k0:k1, g] += P.T @ dO[q0:q1, h]
+    return dQ, dK, dV
+
+
+def bf16_or_f64(x):
+    """uint16 bf16 bit patterns widened exactly to fp64; fp64 arrays as they are."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
 def lse_merge(o_a, lse_a, o_b, lse_b):
     """Two partial attentions of the same queries over disjoint key sets -> attention over the union:
     softmax weights of the union are the partial ones rescaled by exp(LSE_part - LSE_union).

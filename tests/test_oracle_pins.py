@@ -545,3 +545,70 @@ def test_kvshard_dense_brute_force_and_closed_forms():
     assert np.array_equal(Om, On) and np.array_equal(Lm, Ln)
     Om, Lm = oracle.lse_merge(Oe, Le, Oe, Le)
     assert not Om.any() and np.isneginf(Lm).all()
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_kvshard_backward_parts_add_up_to_the_full_backward(causal):
+    """The complete backward (pinned above by finite differences) = the shard backwards of a partition of
+    the keys: the dQ parts add up to dQ, every shard's dK / dV are the complete ones of its keys; also
+    for a chunk of the queries only (then dK / dV of the chunks add up).  Pins attn_bwd_kvshard: a
+    wrong mask offset, a dropped delta, a transposed product or a missing scale breaks the identity."""
+    lens, Hq, Hkv, D = [9, 1, 40, 17, 64], 4, 2, 8
+    cu = wl.cu_seqlens(lens)
+    q, k, v = _shard_inputs(lens, Hq, Hkv, D, 51)
+    dO = np.random.default_rng(52).standard_normal(q.shape)
+    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, dO, cu, causal)
+    delta = np.einsum("thd,thd->ht", dO, O)
+    rng = np.random.default_rng(53)
+    B = len(lens)
+    for trial in range(3):
+        c1 = [int(rng.integers(0, s + 1)) for s in lens]
+        c2 = [int(rng.integers(c, s + 1)) for c, s in zip(c1, lens)]
+        a = [int(rng.integers(0, s + 1)) for s in lens]                    # query chunks: rows 0 .. a-1 and a .. s-1
+        dq_sum = np.zeros_like(dQ)
+        for klo, khi in (([0] * B, c1), (c1, c2), (c2, list(lens))):
+            ks, cu_k = _split(k, cu, klo, khi)
+            vs, _ = _split(v, cu, klo, khi)
+            dk_sum, dv_sum = np.zeros_like(ks), np.zeros_like(vs)
+            for qlo, qhi in (([0] * B, a), (a, list(lens))):
+                qs, cu_q = _split(q, cu, qlo, qhi)
+                gs, _ = _split(dO, cu, qlo, qhi)
+                ls = np.concatenate([LSE[:, int(cu[b]) + qlo[b]: int(cu[b]) + qhi[b]] for b in range(B)], axis=1)
+                ds = np.concatenate([delta[:, int(cu[b]) + qlo[b]: int(cu[b]) + qhi[b]] for b in range(B)], axis=1)
+                shift = [x - l for x, l in zip(qlo, klo)]
+                dq_p, dk_p, dv_p = oracle.attn_bwd_kvshard(qs, ks, vs, gs, ls, ds, cu_q, cu_k, shift, causal)
+                for b in range(B):
+                    dq_sum[int(cu[b]) + qlo[b]: int(cu[b]) + qhi[b]] += dq_p[int(cu_q[b]): int(cu_q[b + 1])]
+                dk_sum += dk_p
+                dv_sum += dv_p
+            assert np.abs(dk_sum - _split(dK, cu, klo, khi)[0]).max(initial=0.0) < 1e-11
+            assert np.abs(dv_sum - _split(dV, cu, klo, khi)[0]).max(initial=0.0) < 1e-11
+        assert np.abs(dq_sum - dQ).max() < 1e-11
+
+
+def test_kvshard_backward_closed_forms():
+    """(1) One query row that sees exactly one key with the complete softmax's statistics: P = 1, delta = dP,
+    so dS = 0: dQ = dK = 0 and dV = dO.  (2) Keys no row sees get dK = dV = 0; rows that see no key of the
+    shard get a zero dQ part.  (3) A row whose log-sum-exp is -inf (no key anywhere) contributes nothing."""
+    D = 4
+    rng = np.random.default_rng(61)
+    q, k, v, g = (rng.standard_normal((1, 1, D)) for _ in range(4))
+    s = float(q[0, 0] @ k[0, 0]) / np.sqrt(D)
+    dq, dk, dv = oracle.attn_bwd_kvshard(q, k, v, g, [[s]], [[float(g[0, 0] @ v[0, 0])]], [0, 1], [0, 1], [0], True)
+    assert np.abs(dq).max() < 1e-15 and np.abs(dk).max() < 1e-15 and np.abs(dv - g).max() < 1e-15
+    sq, sk = 6, 9
+    q, g = rng.standard_normal((sq, 1, D)), rng.standard_normal((sq, 1, D))
+    k, v = rng.standard_normal((sk, 1, D)), rng.standard_normal((sk, 1, D))
+    lse, delta = rng.standard_normal((1, sq)) + 3.0, rng.standard_normal((1, sq))
+    dq, dk, dv = oracle.attn_bwd_kvshard(q, k, v, g, lse, delta, [0, sq], [0, sk], [-2], True)   # key j visible iff j <= i - 2
+    assert not dq[:2].any() and dq[2:].any()            # rows 0, 1 see nothing
+    assert not dk[4:].any() and not dv[4:].any()        # keys 4 .. 8 are seen by no row (i - 2 <= 3)
+    assert dk[:4].any() and dv[:4].any()
+    lse[0, 3] = -np.inf
+    dq2, dk2, dv2 = oracle.attn_bwd_kvshard(q, k, v, g, lse, delta, [0, sq], [0, sk], [-2], True)
+    assert not dq2[3].any() and np.isfinite(dk2).all() and np.isfinite(dv2).all()
+    others = [i for i in range(sq) if i != 3]
+    dq3, dk3, dv3 = oracle.attn_bwd_kvshard(q[others], k, v, g[others], lse[:, others], delta[:, others],
+                                            [0, sq - 1], [0, sk], [-2], False)
+    dq4, dk4, dv4 = oracle.attn_bwd_kvshard(q, k, v, g, lse, delta, [0, sq], [0, sk], [-2], False)
+    assert np.abs(dk3 - dk4).max() < 1e-13 and np.abs(dv3 - dv4).max() < 1e-13

@@ -103,7 +103,8 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     parallelism, and the appendix that integrates it): the device holds the LAST 1/P of every sequence's
     query rows (the rank with the most visible keys, which sets the ring's time), the key/value shards come
     by one at a time (its own first, then the earlier ones), each gives a partial attention
-    (flexsp_attn_varlen_fwd_kvshard) that is folded into the running result (flexsp_lse_merge, in place).
+    (flexsp_attn_varlen_fwd_kvshard) that is folded into the running result (flexsp_lse_merge, in place);
+    then the backward ring (flexsp_attn_varlen_bwd_kvshard with accumulate, fp32 partial sums).
     Plans are built beforehand (lengths are known on the host); timed with events on the stream."""
     cfg = next(c for c in wl.CONFIGS if c.name == workload)
     lens = [s for s in wl.lengths(cfg)]
@@ -165,6 +166,31 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
             prev = ev[r][2 * n + 1]
     fwd_med, mrg_med = np.median(fwd_ms, axis=0), np.median(mrg_ms, axis=0)
     flops = sum(sh["flops"] for sh in shards)
+    # the backward ring: every shard's visit adds its part of dQ to one fp32 buffer and this device's part
+    # of dK / dV to the fp32 buffers that travel with the shard (o_acc / l_acc are the complete O and LSE)
+    g = torch.randn((Tq, H, D), device=dev).to(torch.bfloat16)
+    dq = torch.zeros((Tq, H, D), dtype=torch.float32, device=dev)
+    for sh in shards:
+        sh["dk"] = torch.zeros(sh["k"].shape, dtype=torch.float32, device=dev)
+        sh["dv"] = torch.zeros(sh["v"].shape, dtype=torch.float32, device=dev)
+    bev = [[torch.cuda.Event(enable_timing=True) for _ in range(P + 1)] for _ in range(reps)]
+
+    def backward_pass(marks):
+        if marks: marks[0].record(stream)
+        for n, sh in enumerate(shards):
+            fx.flexsp_attn_varlen_bwd_kvshard(ctx, sh["plan"], q, sh["k"], sh["v"], o_acc, g, l_acc, dq, sh["dk"], sh["dv"],
+                                              accumulate=True, stream=stream)
+            if marks: marks[n + 1].record(stream)
+
+    for _ in range(3):
+        backward_pass(None)
+    torch.cuda.synchronize()
+    for r in range(reps):
+        backward_pass(bev[r])
+    torch.cuda.synchronize()
+    bwd_ms = np.array([[bev[r][n].elapsed_time(bev[r][n + 1]) for n in range(P)] for r in range(reps)])
+    bwd_med = np.median(bwd_ms, axis=0)
+    bwd_total = float(np.median([bev[r][0].elapsed_time(bev[r][P]) for r in range(reps)]))
     merge_bytes = 3 * Tq * H * D * 2 + 3 * H * Tq * 4           # two partial results read, one written
     # the ordinary forward over the unsplit batch, for the rate the shard kernel is measured against
     plan = fx.Plan(ctx, cu, H, Hkv, D, True)
@@ -178,7 +204,15 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     e1.record(stream)
     torch.cuda.synchronize()
     full_ms = e0.elapsed_time(e1) / 3
-    full_flops = wl.attn_flops(lens, H, D, True)[0]
+    full_flops, full_bwd_flops = wl.attn_flops(lens, H, D, True)
+    g_full = torch.randn_like(q_full)
+    dq_f, dk_f, dv_f = torch.empty_like(q_full), torch.empty_like(k), torch.empty_like(v)
+    for i in range(6):
+        if i == 3: e0.record(stream)
+        fx.flexsp_attn_varlen_bwd(ctx, plan, q_full, k, v, o_full, g_full, l_full, cud, dq_f, dk_f, dv_f, stream=stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    full_bwd_ms = e0.elapsed_time(e1) / 3
     plan.close()
     out = {"workload": cfg.name, "ring_degree": P, "query_rows": Tq, "heads": H, "head_dim": D,
            "shards": [{"shard": sh["shard"], "ms": float(fwd_med[n]), "tflops": sh["flops"] / (fwd_med[n] * 1e-3) / 1e12}
@@ -186,7 +220,11 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
            "merge_ms_each": float(np.median(mrg_med[1:])), "merge_GBps": merge_bytes / (np.median(mrg_med[1:]) * 1e-3) / 1e9,
            "pass_ms": total_ms, "pass_tflops": flops / (total_ms * 1e-3) / 1e12,
            "shard_forwards_tflops": flops / (fwd_med.sum() * 1e-3) / 1e12,
-           "unsplit_forward_ms": full_ms, "unsplit_forward_tflops": full_flops / (full_ms * 1e-3) / 1e12}
+           "unsplit_forward_ms": full_ms, "unsplit_forward_tflops": full_flops / (full_ms * 1e-3) / 1e12,
+           "backward_shards": [{"shard": sh["shard"], "ms": float(bwd_med[n]),
+                                "tflops": 2.5 * sh["flops"] / (bwd_med[n] * 1e-3) / 1e12} for n, sh in enumerate(shards)],
+           "backward_pass_ms": bwd_total, "backward_pass_tflops": 2.5 * flops / (bwd_total * 1e-3) / 1e12,
+           "unsplit_backward_ms": full_bwd_ms, "unsplit_backward_tflops": full_bwd_flops / (full_bwd_ms * 1e-3) / 1e12}
     for sh in shards:
         sh["plan"].close()
     return out
@@ -215,7 +253,7 @@ def main() -> int:
                          "(forward + backward) of the workload with one plan; nothing is timed")
     ap.add_argument("--kvshard-ring", action="store_true",
                     help="only the context-parallel leg: one device's ring pass (forward against one key shard at a "
-                         "time + merge) on single-128k (8 shards) and pareto-64k (4 shards), beside the unsplit forward")
+                         "time + merge, then the backward ring) on single-128k (8 shards) and pareto-64k (4 shards), beside the unsplit forward")
     ap.add_argument("--permute-only", action="store_true",
                     help="only the permute bandwidth leg: 50 pack, 50 unpack, 50 plain copies (pack with P = 1), "
                          "in that order (for counter collection)")

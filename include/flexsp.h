@@ -245,7 +245,7 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
  * Attention against ONE SHARD of the keys, and the merge of such partial results: the per-device
  * work of context parallelism (Sec. 2.1.3, paragraph "Context Parallelism": queries, keys and values
  * are split along the sequence, key/value chunks travel round a ring and attention is computed chunk
- * by chunk; the appendix on integrating context parallelism into FlexSP).  Forward only.
+ * by chunk; the appendix on integrating context parallelism into FlexSP).
  *
  * flexsp_plan_create_kvshard - tile plan for B sequences whose QUERIES are rows cu_q[b] .. cu_q[b+1]-1
  *   of q / o / lse and whose shard KEYS are rows cu_k[b] .. cu_k[b+1]-1 of k / v (host pointers, B+1
@@ -253,14 +253,29 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
  *   |shift| <= 2^30) = position of sequence b's first query inside the full sequence minus position of
  *   the shard's first key: with `causal`, shard key j is visible to query row i iff j <= i + shift[b];
  *   without, every shard key is visible and shift is ignored.  The plan serves
- *   flexsp_attn_varlen_fwd_kvshard only (the other attention calls answer PLAN_MISMATCH); it is destroyed
- *   by flexsp_plan_destroy and inspected by flexsp_plan_num_items / _get_items with FLEXSP_PASS_FWD, where
- *   an item's seq_start holds the sequence INDEX b.  Long tiles are cut into parts as in flexsp_plan_create
- *   (a step = 64 shard keys).  Hq <= 65 535, else UNSUPPORTED.
+ *   flexsp_attn_varlen_fwd_kvshard and flexsp_attn_varlen_bwd_kvshard only (the other attention calls
+ *   answer PLAN_MISMATCH); it is destroyed by flexsp_plan_destroy and inspected by flexsp_plan_num_items /
+ *   _get_items, where an item's seq_start holds the sequence INDEX b (and, in FLEXSP_PASS_BWD_DKV, tile
+ *   counts 64-key tiles of the SHARD).  Long query tiles are cut into parts as in flexsp_plan_create (a
+ *   step = 64 shard keys); key tiles are not.  Hq <= 65 535, else UNSUPPORTED.
  *
  * flexsp_attn_varlen_fwd_kvshard - per query row, softmax over the visible shard keys only:
  *   O = sum_j P_j v_j (bf16), LSE = log sum_j exp(scale q.k_j) (fp32, natural log, [head_count, Tq]).
  *   A row that sees no key of the shard gets O = 0 and LSE = -inf.  Arguments as flexsp_attn_varlen_fwd.
+ *
+ * flexsp_attn_varlen_bwd_kvshard - the backward's share of one key shard (gradient of Eq. 3 restricted to
+ *   the shard's keys), for the same plan.  `lse` ([head_count, Tq] fp32, natural log) must be each row's
+ *   log-sum-exp over ALL its keys and `o` the complete output (both as left by the merges of the forward
+ *   ring), so that P_ij = exp(scale q_i.k_j - lse_i) and delta_i = dO_i . o_i are those of the complete
+ *   attention; then, over the visible keys j of the shard,
+ *       dQ_i = scale sum_j dS_ij k_j (this shard's part),  dK_j = scale sum_i dS_ij q_i,  dV_j = sum_i P_ij dO_i,
+ *       dS_ij = P_ij (dO_i.v_j - delta_i).
+ *   dq is [Tq, Hq, D], dk / dv are [Tk, Hkv, D] (rows of the shard), grad_dtype as in flexsp_attn_varlen_bwd.
+ *   accumulate = 0: the three outputs are overwritten (rows and keys that see nothing get zeros);
+ *   accumulate = 1 (fp32 gradients only, else UNSUPPORTED): the results are ADDED to what dq / dk / dv
+ *   hold, as a ring needs it (dq gathers the shards' parts; dk / dv travel with their shard and gather
+ *   the devices' parts).  A row whose lse is -inf contributes nothing.  Deterministic; the plan's scratch
+ *   is used as in flexsp_attn_varlen_bwd (calls on one plan must not overlap).
  *
  * flexsp_lse_merge - two partial results of the same queries over DISJOINT key sets -> the result
  *   over their union:  LSE = log(exp(lse_a) + exp(lse_b)),  O = exp(lse_a - LSE) O_a + exp(lse_b - LSE) O_b
@@ -278,6 +293,12 @@ int flexsp_attn_varlen_fwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_te
                                    flexsp_tensor v, int32_t head_begin, int32_t head_count, int32_t kv_head_begin,
                                    int32_t kv_head_count, int causal, float softmax_scale, flexsp_tensor o,
                                    float *lse, flexsp_stream stream);
+int flexsp_attn_varlen_bwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                                   flexsp_tensor v, flexsp_tensor o, flexsp_tensor dO, const float *lse,
+                                   int32_t head_begin, int32_t head_count, int32_t kv_head_begin,
+                                   int32_t kv_head_count, int causal, float softmax_scale, flexsp_tensor dq,
+                                   flexsp_tensor dk, flexsp_tensor dv, int32_t grad_dtype, int32_t accumulate,
+                                   flexsp_stream stream);
 int flexsp_lse_merge(flexsp_ctx *ctx, flexsp_tensor o_a, const float *lse_a, flexsp_tensor o_b, const float *lse_b,
                      flexsp_tensor o_out, float *lse_out, int64_t T, int32_t H, int32_t D, flexsp_stream stream);
 

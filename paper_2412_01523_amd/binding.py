@@ -26,7 +26,7 @@ EXPORTS = (
     "flexsp_plan_tile_rows", "flexsp_attn_bwd_workspace_bytes",
     "flexsp_pack", "flexsp_unpack", "flexsp_pack_many", "flexsp_unpack_many",
     "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd", "flexsp_attn_varlen_fwd_static",
-    "flexsp_plan_create_kvshard", "flexsp_attn_varlen_fwd_kvshard", "flexsp_lse_merge",
+    "flexsp_plan_create_kvshard", "flexsp_attn_varlen_fwd_kvshard", "flexsp_attn_varlen_bwd_kvshard", "flexsp_lse_merge",
     "flexsp_profile_start", "flexsp_profile_stop",
     "flexsp_bucket_dp", "flexsp_chunk_dp", "flexsp_min_microbatches",
 )
@@ -109,6 +109,9 @@ def lib() -> ctypes.CDLL:
                                                  c_int32, c_int, POINTER(c_void_p)]
         L.flexsp_attn_varlen_fwd_kvshard.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, c_int32, c_int32,
                                                      c_int32, c_int32, c_int, c_float, Tensor, c_void_p, c_void_p]
+        L.flexsp_attn_varlen_bwd_kvshard.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, Tensor, Tensor, c_void_p,
+                                                     c_int32, c_int32, c_int32, c_int32, c_int, c_float, Tensor, Tensor,
+                                                     Tensor, c_int32, c_int32, c_void_p]
         L.flexsp_lse_merge.argtypes = [c_void_p, Tensor, c_void_p, Tensor, c_void_p, Tensor, c_void_p, c_int64,
                                        c_int32, c_int32, c_void_p]
         L.flexsp_bucket_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int32), c_void_p,
@@ -327,6 +330,22 @@ def flexsp_attn_varlen_fwd_kvshard(ctx: Context, plan: ShardPlan, q, k, v, o, ls
                                                 head_count, kv_head_begin, kv_head_count, int(bool(causal)),
                                                 float(softmax_scale), _view(o), lse.data_ptr(), _stream(stream)),
            "flexsp_attn_varlen_fwd_kvshard")
+
+
+def flexsp_attn_varlen_bwd_kvshard(ctx: Context, plan: ShardPlan, q, k, v, o, dO, lse, dq, dk, dv, *, head_begin=0,
+                                   head_count=None, kv_head_begin=0, kv_head_count=None, causal=True, softmax_scale=0.0,
+                                   grad_dtype=None, accumulate=False, stream=None):
+    """lse [Hq,Tq] and o: those of the COMPLETE attention; dq [Tq,Hq,D], dk / dv [Tk,Hkv,D] (see include/flexsp.h)."""
+    import torch
+    head_count = plan.hq if head_count is None else head_count
+    kv_head_count = plan.hkv if kv_head_count is None else kv_head_count
+    if grad_dtype is None:
+        grad_dtype = F32 if dq.dtype == torch.float32 else BF16
+    _check(lib().flexsp_attn_varlen_bwd_kvshard(ctx.handle, plan.handle, _view(q), _view(k), _view(v), _view(o), _view(dO),
+                                                lse.data_ptr(), head_begin, head_count, kv_head_begin, kv_head_count,
+                                                int(bool(causal)), float(softmax_scale), _view(dq), _view(dk), _view(dv),
+                                                grad_dtype, int(bool(accumulate)), _stream(stream)),
+           "flexsp_attn_varlen_bwd_kvshard")
 
 
 def flexsp_lse_merge(ctx: Context, o_a, lse_a, o_b, lse_b, o_out, lse_out, stream=None):

@@ -37,7 +37,12 @@ constexpr int kReadAhead = 4;
 // swapped through LDS: a fragment is written and read back by the same lane numbers, so the swap
 // is a plain linear copy.  No matrix work is duplicated, every wavefront fits in 256 registers,
 // and two workgroups share a CU.
-template <int D>
+//
+// SHARD = true is the variant for one shard of the keys (context parallelism; see the forward kernel):
+// an item names 64 keys of the shard and the query rows of its sequence on this device, key j is
+// visible to query row i iff j <= i + shift, the rows' log-sum-exp and delta are those of the COMPLETE
+// attention, and the gradients may be added to what dK / dV hold.  Tiles are not cut into parts.
+template <int D, bool SHARD>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArgs a)
 {
     typedef LdsTile<D> L;
@@ -70,23 +75,36 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
     ItemDealer deal;
 
     for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
-        const flexsp_item it = load_item(a.pq.items, item);
+        // s: query rows of the sequence; sk: its keys; sh: position of the first query minus position of
+        // the first key (0 unless SHARD); tok0 / ktok0: their first rows in q, dO / k, v
+        int s, sk, sh, g, kv0, first, total, nparts, part, slot, qfirst, nsteps;
+        int64_t tok0, ktok0;
+        if constexpr (SHARD) {
+            const flexsp_shard_item it = load_shard_item((const flexsp_shard_item *)a.pq.items, item);
+            s = it.q_len; sk = it.k_len; sh = it.shift; g = it.head_parts & 0xffff; kv0 = it.tile * kDkvBk;
+            tok0 = it.q_start; ktok0 = it.k_start;
+            // the first query row that sees the tile's first key, rounded down to a step boundary; no
+            // steps at all when no row of the device sees these keys
+            qfirst = a.causal ? (max(0, kv0 - sh) & ~(BQ - 1)) : 0;
+            nsteps = max(0, (s - qfirst + BQ - 1) / BQ);
+            first = 0; total = nsteps * a.G; nparts = 1; part = 0; slot = -1;
+        } else {
+            const flexsp_item it = load_item(a.pq.items, item);
+            s = it.seq_len; sk = s; sh = 0; g = it.head; kv0 = it.tile * kDkvBk;
+            tok0 = it.seq_start; ktok0 = tok0;
+            qfirst = a.causal ? kv0 : 0;  // kv0 is a multiple of BQ
+            nsteps = (s - qfirst + BQ - 1) / BQ;
+            // the item walks steps `first` .. `total`-1 of the tile's nsteps * G (all of them unless the tile was cut)
+            first = it.step_begin; total = it.step_end;
+            nparts = it.parts & 0xffff; part = it.parts >> 16; slot = it.slot;
+        }
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
         int lane = lane0;
         asm volatile("" : "+v"(lane));
         const int r = lane & 31, hl = lane >> 5;
-        const int s = it.seq_len, g = it.head;
-        const int kv0 = it.tile * kDkvBk;
-        const int64_t tok0 = it.seq_start;
         const int wk_lo = kv0 + kb * 32;
         const int kvrow = wk_lo + r;  // this lane's key (column of S)
-
-        const int qfirst = a.causal ? kv0 : 0;  // kv0 is a multiple of BQ
-        const int nsteps = (s - qfirst + BQ - 1) / BQ;
-        // the item walks steps `first` .. `total`-1 of the tile's nsteps * G (all of them unless the tile was cut)
-        const int first = it.step_begin, total = it.step_end;
-        const int nparts = it.parts & 0xffff, part = it.parts >> 16;
 
         const uint32_t goffq = tile_goff<D>(a.q_st, wave, lane), goffg = tile_goff<D>(a.do_st, wave, lane);
         // Steps are counted from the item's first one (n of them); which head and which query rows a step
@@ -99,7 +117,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
         // it, does not show).
         if (n < kLateTicketSteps) deal.prefetch();
         const int q_end = qfirst + nsteps * BQ;
-        int h_cur = g * a.G + first / nsteps, q_cur = qfirst + (first % nsteps) * BQ;
+        int h_cur = g * a.G + (SHARD ? 0 : first / nsteps), q_cur = qfirst + (SHARD ? 0 : (first % nsteps) * BQ);
         int h_nxt = h_cur, q_nxt = q_cur;
         auto advance_nxt = [&]() {
             q_nxt += BQ;
@@ -132,8 +150,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
         bf16x8 kf[KS], vf[KS];
         {
             RowBlock<D> krows, vrows;
-            krows.load(a.k + tok0 * a.k_st + (int64_t)g * a.k_sh, a.k_st, wk_lo, s - 1, lane);
-            vrows.load(a.v + tok0 * a.v_st + (int64_t)g * a.v_sh, a.v_st, wk_lo, s - 1, lane);
+            krows.load(a.k + ktok0 * a.k_st + (int64_t)g * a.k_sh, a.k_st, wk_lo, sk - 1, lane);
+            vrows.load(a.v + ktok0 * a.v_st + (int64_t)g * a.v_sh, a.v_st, wk_lo, sk - 1, lane);
             // (this kernel's fragment offsets point at row block j of a tile: wavefronts 2kb and 2kb+1 use
             // the two halves of one 64-row stretch, so the stretch's address serves both)
             char *stretch = smem + STEP + kb * (64 * L::ROWB);
@@ -157,7 +175,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
             // sequence or wholly above the diagonal; both wavefronts of a pair agree on that
             auto empty = [&](int qb) {
                 const int lo_ = q_lo + qb * 32;
-                return lo_ >= s || (a.causal && lo_ + 31 < wk_lo);
+                return lo_ >= s || (a.causal && lo_ + 31 + sh < wk_lo);
             };
             lo.pin();
             wait_vmem();
@@ -206,7 +224,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                 __builtin_amdgcn_s_setprio(0);
                 if (__builtin_expect(step + 1 < n, 1)) prefetch(h_nxt, q_nxt, BUF ^ 1);
                 // rows of the accumulator: query my_lo + 8*i4 + 4*hl + e
-                const bool masked = (a.causal && my_lo < wk_lo + 31) || (my_lo + 32 > s);
+                const bool masked = (a.causal && my_lo + sh < wk_lo + 31) || (my_lo + 32 > s);
                 auto probs = [&](auto maskc) {
                     constexpr bool MASK = decltype(maskc)::value;
 #pragma unroll
@@ -218,7 +236,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
                             p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[4 * i4 + e], a.scale_l2, -l4[e]));
                             if (MASK) {
                                 const int qr = my_lo + 8 * i4 + 4 * hl + e;
-                                p[e] = ((a.causal && qr < kvrow) || qr >= s) ? 0.f : p[e];
+                                p[e] = ((a.causal && qr + sh < kvrow) || qr >= s) ? 0.f : p[e];
                             }
                             ds[e] = p[e] * pacc[4 * i4 + e];
                         }
@@ -282,27 +300,29 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
         }
         if (n >= kLateTicketSteps) deal.prefetch();
         if (nparts > 1) {
-            split_store<DB>(a.pq.split_scratch + (int64_t)(it.slot + part) * kPartialBytes, accT, tid);
-            if (!split_arrive(a.pq.split_flags + it.slot, nparts, &split_word, tid)) continue;  // a later part finishes the tile
+            split_store<DB>(a.pq.split_scratch + (int64_t)(slot + part) * kPartialBytes, accT, tid);
+            if (!split_arrive(a.pq.split_flags + slot, nparts, &split_word, tid)) continue;  // a later part finishes the tile
 #pragma unroll
             for (int d = 0; d < DB; d++)
 #pragma unroll
                 for (int i = 0; i < 16; i++) accT[d][i] = 0.f;
             for (int p = 0; p < nparts; p++)
-                split_sum<DB>(a.pq.split_scratch + (int64_t)(it.slot + p) * kPartialBytes, accT, 1.0f, tid);
+                split_sum<DB>(a.pq.split_scratch + (int64_t)(slot + p) * kPartialBytes, accT, 1.0f, tid);
         }
 
         // role 0 writes dV rows, role 1 writes dK rows (scaled)
         char *const out = (char *)(j ? a.dk : a.dv);
         const int64_t ost = j ? a.dk_st : a.dv_st, osh = j ? a.dk_sh : a.dv_sh;
         const float mul = j ? a.scale : 1.0f;
-        if (a.grad_f32) {
-            if (kvrow < s) store_rowT<DB>(out + ((tok0 + kvrow) * ost + (int64_t)g * osh) * 4, true, accT, mul, hl);
-        } else if (wk_lo < s) {
+        if (SHARD && (a.grad_f32 & 2)) {  // added to the partial sums the rows hold
+            if (kvrow < sk) add_rowT_f32<DB>((float *)out + (ktok0 + kvrow) * ost + (int64_t)g * osh, accT, mul, hl);
+        } else if (a.grad_f32) {
+            if (kvrow < sk) store_rowT<DB>(out + ((ktok0 + kvrow) * ost + (int64_t)g * osh) * 4, true, accT, mul, hl);
+        } else if (wk_lo < sk) {
             // through the Q/dO buffer the last step did not use (every wavefront is past its barriers)
             store_rowT_bf16_lds<DB>(smem + (n & 1) * STEP + wave * (32 * L::ROWB),
-                                    (uint16_t *)out + (tok0 + wk_lo) * ost + (int64_t)g * osh, ost,
-                                    min(32, s - wk_lo), accT, mul, lane);
+                                    (uint16_t *)out + (ktok0 + wk_lo) * ost + (int64_t)g * osh, ost,
+                                    min(32, sk - wk_lo), accT, mul, lane);
         }
         // deal.advance() holds the barrier after which the tiles and the exchange slots are reused
     }
@@ -310,7 +330,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dkv_kernel(const AttnArg
 }
 
 // ------------------------------------------------------------------------------ dQ
-template <int D>
+// SHARD = true: the rows' share of dQ that comes from one shard of the keys (see the dK/dV kernel): the
+// log-sum-exp read here is that of the complete attention and `o` the complete output, so delta is the
+// complete one; a part of a cut tile comes as an item of its own with its key range and shift.
+template <int D, bool SHARD>
 __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs a)
 {
     typedef LdsTile<D> L;
@@ -328,22 +351,37 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
     ItemDealer deal;
 
     for (int item = deal.first(a.pq, &deal_word, wave, lane0); item >= 0; item = deal.advance()) {
-        const flexsp_item it = load_item(a.pq.items, item);
+        // s: query rows of the sequence; sk: keys counted from the item's first one; rel: position of a
+        // row among those keys minus its row index; tok0 / ktok0: first rows in q, o, dO / k, v
+        int s, sk, rel, h, q0, ntiles, nparts, part, slot;
+        int64_t tok0, ktok0;
+        if constexpr (SHARD) {
+            const flexsp_shard_item it = load_shard_item((const flexsp_shard_item *)a.pq.items, item);
+            s = it.q_len; sk = it.k_len; rel = it.shift; h = it.head_parts & 0xffff; q0 = it.tile * kDqBq;
+            tok0 = it.q_start; ktok0 = it.k_start;
+            part = (it.head_parts >> 16) & 0xff; nparts = it.head_parts >> 24; slot = it.slot;
+            const int kv_end = a.causal ? max(0, min(sk, q0 + kDqBq + rel)) : sk;  // keys some row of the tile sees
+            ntiles = (kv_end + kDqBk - 1) / kDqBk;
+        } else {
+            const flexsp_item it = load_item(a.pq.items, item);
+            s = it.seq_len; h = it.head; q0 = it.tile * kDqBq;
+            tok0 = it.seq_start;
+            // The item walks key tiles step_begin .. step_end-1 (all of them unless the tile was cut: then it
+            // hands its partial dQ over).  From here on keys are counted from the item's first one: koff keys
+            // are skipped, `sk` remain, and a row's own position among them is its row index minus koff.
+            const int koff = it.step_begin * kDqBk;
+            ntiles = it.step_end - it.step_begin; sk = s - koff; rel = -koff;
+            ktok0 = tok0 + koff;
+            nparts = it.parts & 0xffff; part = it.parts >> 16; slot = it.slot;
+        }
         // opaque per-item copy of the lane id: per-lane address arithmetic of an item stays inside
         // the item instead of being hoisted out of this loop into long-lived registers
         int lane = lane0;
         asm volatile("" : "+v"(lane));
         const int r = lane & 31, hl = lane >> 5;
-        const int s = it.seq_len, h = it.head, g = h / a.G;
-        const int q0 = it.tile * kDqBq;
-        const int64_t tok0 = it.seq_start;
-        // The item walks key tiles step_begin .. step_end-1 (all of them unless the tile was cut: then it
-        // hands its partial dQ over).  From here on keys are counted from the item's first one: koff keys
-        // are skipped, `sk` remain, and a row's own position among them is its row index minus koff.
-        const int koff = it.step_begin * kDqBk, ntiles = it.step_end - it.step_begin, sk = s - koff;
-        const int nparts = it.parts & 0xffff, part = it.parts >> 16;
-        const uint16_t *kbase = a.k + (tok0 + koff) * a.k_st + (int64_t)g * a.k_sh;
-        const uint16_t *vbase = a.v + (tok0 + koff) * a.v_st + (int64_t)g * a.v_sh;
+        const int g = h / a.G;
+        const uint16_t *kbase = a.k + ktok0 * a.k_st + (int64_t)g * a.k_sh;
+        const uint16_t *vbase = a.v + ktok0 * a.v_st + (int64_t)g * a.v_sh;
         const uint32_t goffk = tile_goff<D>(a.k_st, wave, lane), goffv = tile_goff<D>(a.v_st, wave, lane);
         auto prefetch = [&](int t, int buf) {
             char *dk = smem + buf * 2 * TILE, *dv = dk + TILE;
@@ -355,11 +393,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
                 load_tile_async<D, kDqBk>(dv, vbase, a.v_st, t * kDqBk, sk - 1, wave, lane);
             }
         };
-        prefetch(0, 0);
+        if (!SHARD || ntiles > 0) prefetch(0, 0);  // (a tile of a shard's queries may see none of its keys)
 
         const int qrow = q0 + wave * 32 + r;
         const int wq_lo = q0 + wave * 32;
-        const int wq_rel = wq_lo - koff;  // the wavefront's first row, counted like the keys
+        const int wq_rel = wq_lo + rel;  // the wavefront's first row, counted like the keys
         const bool qok = qrow < s;
         bf16x8 qf[KS], gf[KS];  // B operands: column = query row, k = head dim
         // delta = dO . O of the row (the backward's preprocessing step, done here because this kernel
@@ -395,7 +433,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
         const float delta = halves_sum(dpart);
         // the log-sum-exp in base 2, so that the recomputation is one fma + exp2 per score; +inf makes
         // P = 0 for rows past the end of the sequence
-        const float lse2 = qok ? a.lse_in[(int64_t)h * a.T + tok0 + qrow] * 1.4426950408889634f : INFINITY;
+        float lse2 = qok ? a.lse_in[(int64_t)h * a.T + tok0 + qrow] * 1.4426950408889634f : INFINITY;
+        if constexpr (SHARD) lse2 = lse2 == -INFINITY ? INFINITY : lse2;  // a row that saw no key anywhere
 
         f32x16 dqT[DB];  // rows = head dim, column = query
 #pragma unroll
@@ -417,8 +456,9 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
             if (__builtin_expect(t + 1 < ntiles, 1)) prefetch(t + 1, BUF ^ 1);
             if (a.causal && kv0 > wq_rel + 31) return;
 
-            const bool need_mask = a.causal ? (kv0 + kDqBk - 1 > wq_rel) : (kv0 + kDqBk > sk);
-            const int lim = a.causal ? qrow - koff : sk - 1;
+            const bool need_mask = SHARD ? ((a.causal && kv0 + kDqBk - 1 > wq_rel) || kv0 + kDqBk > sk)
+                                         : (a.causal ? (kv0 + kDqBk - 1 > wq_rel) : (kv0 + kDqBk > sk));
+            const int lim = SHARD ? (a.causal ? min(qrow + rel, sk - 1) : sk - 1) : (a.causal ? qrow + rel : sk - 1);
             // one 32-key block at a time (keeps the register count under half the file)
 #pragma unroll
             for (int kb = 0; kb < 2; kb++) {
@@ -495,16 +535,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
             a.lse_out[(int64_t)h * a.T + tok0 + qrow] = lse2;
         }
         if (nparts > 1) {
-            split_store<DB>(a.pq.split_scratch + (int64_t)(it.slot + part) * kPartialBytes, dqT, tid);
-            if (!split_arrive(a.pq.split_flags + it.slot, nparts, &split_word, tid)) continue;  // a later part finishes the tile
+            split_store<DB>(a.pq.split_scratch + (int64_t)(slot + part) * kPartialBytes, dqT, tid);
+            if (!split_arrive(a.pq.split_flags + slot, nparts, &split_word, tid)) continue;  // a later part finishes the tile
 #pragma unroll
             for (int db = 0; db < DB; db++)
 #pragma unroll
                 for (int i = 0; i < 16; i++) dqT[db][i] = 0.f;
             for (int p = 0; p < nparts; p++)
-                split_sum<DB>(a.pq.split_scratch + (int64_t)(it.slot + p) * kPartialBytes, dqT, 1.0f, tid);
+                split_sum<DB>(a.pq.split_scratch + (int64_t)(slot + p) * kPartialBytes, dqT, 1.0f, tid);
         }
-        if (a.grad_f32) {
+        if (SHARD && (a.grad_f32 & 2)) {  // added to the partial sum the rows hold
+            if (qok)
+                add_rowT_f32<DB>((float *)a.dq + (tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh, dqT, a.scale, hl);
+        } else if (a.grad_f32) {
             if (qok)
                 store_rowT<DB>((char *)a.dq + ((tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh) * 4, true, dqT,
                                a.scale, hl);
@@ -524,18 +567,36 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const AttnArgs
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s)
 {
     if (D == 128)
-        hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, dim3(grid), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, false>), dim3(grid), dim3(kThreads), 0, s, a);
     else
-        hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, dim3(grid), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, false>), dim3(grid), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s)
 {
     if (D == 128)
-        hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, dim3(grid), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<128, false>), dim3(grid), dim3(kThreads), 0, s, a);
     else
-        hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, dim3(grid), dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<64, false>), dim3(grid), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd_dkv_kvshard(const AttnArgs &a, int D, int grid, hipStream_t s)
+{
+    if (D == 128)
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<128, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<64, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd_dq_kvshard(const AttnArgs &a, int D, int grid, hipStream_t s)
+{
+    if (D == 128)
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<128, true>), dim3(grid), dim3(kThreads), 0, s, a);
+    else
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<64, true>), dim3(grid), dim3(kThreads), 0, s, a);
     return hipGetLastError();
 }
 

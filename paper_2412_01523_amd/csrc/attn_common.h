@@ -338,6 +338,23 @@ __device__ __forceinline__ void store_rowT(void *row, bool f32, const f32x16 (&a
         }
 }
 
+// The same for fp32 rows that already hold a partial sum: row += acc * mul (each lane owns its
+// row's elements, so the read-modify-write races with nobody inside the kernel).
+template <int DB>
+__device__ __forceinline__ void add_rowT_f32(float *row, const f32x16 (&acc)[DB], float mul, int hl)
+{
+#pragma unroll
+    for (int db = 0; db < DB; db++)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; i4++) {
+            f32x4 *p = (f32x4 *)(row + db * 32 + 8 * i4 + 4 * hl);
+            f32x4 w = *p;
+#pragma unroll
+            for (int e = 0; e < 4; e++) w[e] += acc[db][4 * i4 + e] * mul;
+            *p = w;
+        }
+}
+
 // Epilogue store of a transposed accumulator as bf16 THROUGH LDS, so that global memory sees
 // whole 16-byte pieces of contiguous rows instead of 8-byte pieces scattered over 32 rows (which
 // the address coalescer handles one lane at a time: thousands of cycles per item).

@@ -461,7 +461,7 @@ int plan_upload(flexsp_ctx *ctx, flexsp_plan *p)
                     const flexsp_item &it = p->pass[i].items[n];
                     const int b = it.seq_start;
                     // a part of a cut tile: the keys of its steps only, positions counted from its first key
-                    const int32_t np = it.parts & 0xffff, part = it.parts >> 16;
+                    const int32_t np = it.parts & 0xffff, part = it.parts >> 16;  // (whole tiles only in the dK/dV pass)
                     const int32_t skip = np > 1 ? it.step_begin * kFwdBk : 0;
                     int32_t k_len = p->cu_k[b + 1] - p->cu_k[b];
                     if (np > 1 && part + 1 < np) k_len = std::min(k_len, it.step_end * kFwdBk);
@@ -712,44 +712,75 @@ int flexsp_plan_create_kvshard(flexsp_ctx *ctx, const int32_t *cu_q, const int32
     p->kvshard = true;
     p->dev_base = nullptr; p->dev_bytes = 0; p->delta = nullptr;
     p->uploaded = false; p->used = false; p->multi_stream = false; p->last_stream = nullptr;
-    p->delta_bytes = 0;  // forward only: no backward scratch
+    p->delta_bytes = 2 * (size_t)p->T * Hq * sizeof(float);  // delta and log2-domain LSE of the query rows
+    static_assert(kFwdBq == kDqBq && kFwdBk == kDqBk, "the forward's and the dQ kernel's shard items are listed alike");
     try {
         p->cu.assign(cu_q, cu_q + B + 1);
         p->cu_k.assign(cu_k, cu_k + B + 1);
         p->shift.assign(shift, shift + B);
-        // items: (sequence index, query tile, head); cost = key tiles the tile's rows can see
-        std::vector<Work> work;
-        std::vector<int64_t> group_cost;
-        for (int b = 0; b < B; b++) {
-            const int32_t sq = cu_q[b + 1] - cu_q[b], sk = cu_k[b + 1] - cu_k[b];
-            if (sq <= 0) continue;
-            const int32_t nt = (int32_t)cdiv(sq, kFwdBq);
-            for (int h = 0; h < Hq; h++) {
-                const int32_t gid = (int32_t)group_cost.size();
-                int64_t gc = 0;
-                for (int32_t t = 0; t < nt; t++) {
-                    int64_t keys = sk;
-                    if (causal) keys = std::max<int64_t>(0, std::min<int64_t>(sk, (int64_t)(t + 1) * kFwdBq + shift[b]));
-                    Work w;
-                    w.it.seq_start = b;  // the sequence INDEX (see plan_upload); its ranges are in cu / cu_k / shift
-                    w.it.seq_len = sq;
-                    w.it.tile = t;
-                    w.it.head = h;
-                    w.cost = cdiv(keys, kFwdBk) + 1;  // an item without visible keys still writes its rows
-                    w.group = gid;
-                    work.push_back(w);
-                    gc += w.cost;
+        // forward and dQ kernel: items (sequence index, query tile, head); cost = key tiles the tile's rows can see
+        for (int pass : {FLEXSP_PASS_FWD, FLEXSP_PASS_BWD_DQ}) {
+            std::vector<Work> work;
+            std::vector<int64_t> group_cost;
+            for (int b = 0; b < B; b++) {
+                const int32_t sq = cu_q[b + 1] - cu_q[b], sk = cu_k[b + 1] - cu_k[b];
+                if (sq <= 0) continue;
+                const int32_t nt = (int32_t)cdiv(sq, kFwdBq);
+                for (int h = 0; h < Hq; h++) {
+                    const int32_t gid = (int32_t)group_cost.size();
+                    int64_t gc = 0;
+                    for (int32_t t = 0; t < nt; t++) {
+                        int64_t keys = sk;
+                        if (causal) keys = std::max<int64_t>(0, std::min<int64_t>(sk, (int64_t)(t + 1) * kFwdBq + shift[b]));
+                        Work w;
+                        w.it.seq_start = b;  // the sequence INDEX (see plan_upload); its ranges are in cu / cu_k / shift
+                        w.it.seq_len = sq;
+                        w.it.tile = t;
+                        w.it.head = h;
+                        w.cost = cdiv(keys, kFwdBk) + 1;  // an item without visible keys still writes its rows
+                        w.group = gid;
+                        work.push_back(w);
+                        gc += w.cost;
+                    }
+                    group_cost.push_back(gc);
                 }
-                group_cost.push_back(gc);
             }
+            // (a tile is cut only when it would outlast TWO even shares: with a share of a few dozen steps, as
+            // on a micro-batch split over a ring, the hand-over of the parts costs more than the wait for a
+            // tile that is a little longer than the rest)
+            distribute(work, group_cost, ctx->num_xcd, workgroups_of(ctx), kFwdBq, p->pass[pass], 2);
         }
-        // (a tile is cut only when it would outlast TWO even shares: with a share of a few dozen steps, as
-        // on a micro-batch split over a ring, the hand-over of the parts costs more than the wait for a
-        // tile that is a little longer than the rest)
-        distribute(work, group_cost, ctx->num_xcd, workgroups_of(ctx), kFwdBq, p->pass[FLEXSP_PASS_FWD], 2);
-        for (int i = 1; i < 3; i++) {
-            for (int x = 0; x <= kMaxQueues; x++) p->pass[i].offsets[x] = 0;
-            p->pass[i].tile_rows = 0;
+        // dK/dV kernel: items (sequence index, key tile of the shard, kv head); cost = steps of 64 query rows
+        // from the first row that sees the tile, for every query head of the group.  Not cut into parts.
+        {
+            std::vector<Work> work;
+            std::vector<int64_t> group_cost;
+            const int G = Hq / Hkv;
+            for (int b = 0; b < B; b++) {
+                const int32_t sq = cu_q[b + 1] - cu_q[b], sk = cu_k[b + 1] - cu_k[b];
+                if (sk <= 0) continue;
+                const int32_t nt = (int32_t)cdiv(sk, kDkvBk);
+                for (int g = 0; g < Hkv; g++) {
+                    const int32_t gid = (int32_t)group_cost.size();
+                    int64_t gc = 0;
+                    for (int32_t t = 0; t < nt; t++) {
+                        int64_t qfirst = 0;
+                        if (causal) qfirst = std::max<int64_t>(0, (int64_t)t * kDkvBk - shift[b]) / kDkvBq * kDkvBq;
+                        Work w;
+                        w.it.seq_start = b;
+                        w.it.seq_len = sk;
+                        w.it.tile = t;
+                        w.it.head = g;
+                        w.cost = std::max<int64_t>(0, cdiv((int64_t)sq - qfirst, kDkvBq)) * G + 1;  // (the rows are written even if nobody sees them)
+                        w.group = gid;
+                        work.push_back(w);
+                        gc += w.cost;
+                    }
+                    group_cost.push_back(gc);
+                }
+            }
+            // (one "workgroup" whose share no tile exceeds: nothing is cut)
+            distribute(work, group_cost, ctx->num_xcd, 1, kDkvBk, p->pass[FLEXSP_PASS_BWD_DKV], 1);
         }
     } catch (const std::bad_alloc &) {
         delete p;
@@ -987,6 +1018,77 @@ int flexsp_attn_varlen_fwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_te
     {
         Timed tm(ctx, FLEXSP_K_FWD, (hipStream_t)stream);
         e = launch_attn_fwd_kvshard(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_FWD], 2), (hipStream_t)stream);
+    }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
+int flexsp_attn_varlen_bwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                                   flexsp_tensor v, flexsp_tensor o, flexsp_tensor dO, const float *lse,
+                                   int32_t head_begin, int32_t head_count, int32_t kv_head_begin,
+                                   int32_t kv_head_count, int causal, float scale, flexsp_tensor dq, flexsp_tensor dk,
+                                   flexsp_tensor dv, int32_t grad_dtype, int32_t accumulate, flexsp_stream stream)
+{
+    if (!ctx || !plan) return FLEXSP_INVALID_ARGUMENT;
+    if (plan->ctx != ctx || !plan->kvshard) return FLEXSP_PLAN_MISMATCH;
+    if (head_begin < 0 || kv_head_begin < 0 || head_count <= 0 || kv_head_count <= 0) return FLEXSP_INVALID_ARGUMENT;
+    if (head_count % kv_head_count != 0) return FLEXSP_INVALID_ARGUMENT;
+    if (head_count != plan->Hq || kv_head_count != plan->Hkv || (causal != 0) != (plan->causal != 0))
+        return FLEXSP_PLAN_MISMATCH;
+    if (grad_dtype != FLEXSP_BF16 && grad_dtype != FLEXSP_F32) return FLEXSP_UNSUPPORTED;
+    if (accumulate != 0 && accumulate != 1) return FLEXSP_INVALID_ARGUMENT;
+    if (accumulate && grad_dtype != FLEXSP_F32) return FLEXSP_UNSUPPORTED;  // partial sums are kept in fp32
+    const bool views = view_ok(q) && view_ok(k) && view_ok(v) && view_ok(o) && view_ok(dO) && view_ok(dq) &&
+                       view_ok(dk) && view_ok(dv) && lse;
+    if (!views || !std::isfinite(scale)) return FLEXSP_INVALID_ARGUMENT;
+    if (ctx->device < 0 || !plan->dev_base) return FLEXSP_NO_DEVICE;
+    if (plan->pass[FLEXSP_PASS_BWD_DQ].items.empty() && plan->pass[FLEXSP_PASS_BWD_DKV].items.empty()) return FLEXSP_OK;
+    {
+        hipError_t pe = plan_before_launch(plan, (hipStream_t)stream);
+        if (pe != hipSuccess) return hip_fail(pe);
+    }
+    if (scale <= 0.f) scale = 1.0f / std::sqrt((float)plan->D);
+    AttnArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.q = (const uint16_t *)q.ptr + (int64_t)head_begin * q.stride_head;
+    a.k = (const uint16_t *)k.ptr + (int64_t)kv_head_begin * k.stride_head;
+    a.v = (const uint16_t *)v.ptr + (int64_t)kv_head_begin * v.stride_head;
+    a.o = (const uint16_t *)o.ptr + (int64_t)head_begin * o.stride_head;
+    a.dO = (const uint16_t *)dO.ptr + (int64_t)head_begin * dO.stride_head;
+    const int64_t gb = grad_dtype == FLEXSP_F32 ? 4 : 2;
+    a.grad_f32 = (grad_dtype == FLEXSP_F32 ? 1 : 0) | (accumulate ? 2 : 0);
+    a.dq = (char *)dq.ptr + (int64_t)head_begin * dq.stride_head * gb;
+    a.dk = (char *)dk.ptr + (int64_t)kv_head_begin * dk.stride_head * gb;
+    a.dv = (char *)dv.ptr + (int64_t)kv_head_begin * dv.stride_head * gb;
+    a.q_st = (int32_t)q.stride_token; a.q_sh = (int32_t)q.stride_head;
+    a.k_st = (int32_t)k.stride_token; a.k_sh = (int32_t)k.stride_head;
+    a.v_st = (int32_t)v.stride_token; a.v_sh = (int32_t)v.stride_head;
+    a.o_st = (int32_t)o.stride_token; a.o_sh = (int32_t)o.stride_head;
+    a.do_st = (int32_t)dO.stride_token; a.do_sh = (int32_t)dO.stride_head;
+    a.dq_st = (int32_t)dq.stride_token; a.dq_sh = (int32_t)dq.stride_head;
+    a.dk_st = (int32_t)dk.stride_token; a.dk_sh = (int32_t)dk.stride_head;
+    a.dv_st = (int32_t)dv.stride_token; a.dv_sh = (int32_t)dv.stride_head;
+    float *lse2 = plan->delta + (size_t)plan->T * plan->Hq;
+    a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
+    a.scale = scale; a.scale_l2 = scale * 1.4426950408889634f;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    // as in flexsp_attn_varlen_bwd: the dQ kernel leaves delta and the base-2 log-sum-exp of its rows in
+    // the plan's scratch for the dK/dV kernel
+    a.lse_in = lse;
+    a.lse_out = lse2;
+    a.delta_out = plan->delta;
+    a.pq = plan->dq[FLEXSP_PASS_BWD_DQ];
+    if (!plan->pass[FLEXSP_PASS_BWD_DQ].items.empty()) {
+        Timed tm(ctx, FLEXSP_K_BWD_DQ, s);
+        e = launch_attn_bwd_dq_kvshard(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DQ], 2), s);
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    a.lse_in = lse2;
+    a.delta_in = plan->delta;
+    a.pq = plan->dq[FLEXSP_PASS_BWD_DKV];
+    if (!plan->pass[FLEXSP_PASS_BWD_DKV].items.empty()) {
+        Timed tm(ctx, FLEXSP_K_BWD_DKV, s);
+        e = launch_attn_bwd_dkv_kvshard(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_BWD_DKV], 2), s);
     }
     return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
 }

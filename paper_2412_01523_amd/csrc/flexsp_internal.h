@@ -68,7 +68,7 @@ struct AttnArgs {
     int32_t Hq;      // query heads in the subset
     int32_t G;       // query heads per kv head
     int32_t causal;
-    int32_t grad_f32;  // gradients are stored as fp32 instead of bf16
+    int32_t grad_f32;  // bit 0: gradients are stored as fp32 instead of bf16; bit 1 (key-shard kernels): added to what is there
     float scale;     // softmax scale
     float scale_l2;  // scale * log2(e)
     PassQueues pq;
@@ -86,6 +86,8 @@ hipError_t launch_lse_merge(const uint16_t *oa, const float *la, const uint16_t 
                             int32_t ob_sh, int32_t oo_st, int32_t oo_sh, hipStream_t s);
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s);
+hipError_t launch_attn_bwd_dkv_kvshard(const AttnArgs &a, int D, int grid, hipStream_t s);  // a.pq.items: flexsp_shard_item;
+hipError_t launch_attn_bwd_dq_kvshard(const AttnArgs &a, int D, int grid, hipStream_t s);   // a.grad_f32 bit 1: add to dq / dk / dv
 
 // Host helpers shared by the files that hold entry points.
 int ctx_device(const flexsp_ctx *ctx);        // HIP device of a context, -1 for a host-only one

@@ -18,6 +18,8 @@ hipError_t launch_attn_fwd(const AttnArgs &, int, int, hipStream_t) { return hip
 hipError_t launch_attn_fwd_kvshard(const AttnArgs &, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_attn_bwd_dkv(const AttnArgs &, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_attn_bwd_dq(const AttnArgs &, int, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_attn_bwd_dkv_kvshard(const AttnArgs &, int, int, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_attn_bwd_dq_kvshard(const AttnArgs &, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_lse_merge(const uint16_t *, const float *, const uint16_t *, const float *, uint16_t *, float *, int64_t,
                             int, int, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, hipStream_t) { return hipErrorUnknown; }
 hipError_t static_scratch_init(int) { return hipErrorUnknown; }
@@ -58,6 +60,13 @@ int main()
         std::vector<flexsp_item> items((size_t)n + 1);
         CHECK(flexsp_plan_get_items(p, FLEXSP_PASS_FWD, items.data(), n, nullptr) == FLEXSP_OK);
         for (int64_t i = 0; i < n; i++) CHECK(items[i].seq_start >= 0 && items[i].seq_start < B);
+        for (int pass : {FLEXSP_PASS_BWD_DKV, FLEXSP_PASS_BWD_DQ}) {
+            const int64_t m = flexsp_plan_num_items(p, pass);
+            CHECK(m >= 0);
+            std::vector<flexsp_item> more((size_t)m + 1);
+            CHECK(flexsp_plan_get_items(p, pass, more.data(), m, nullptr) == FLEXSP_OK);
+            for (int64_t i = 0; i < m; i++) CHECK(more[i].seq_start >= 0 && more[i].seq_start < B);
+        }
         flexsp_plan_destroy(p);
     }
     // validation paths of the hot calls (nothing is launched: the context is host-only)
@@ -72,6 +81,17 @@ int main()
         CHECK(flexsp_attn_varlen_fwd(ctx, p, bad, t, t, nullptr, 0, 2, 0, 2, 1, 0.f, t, lse, nullptr) == FLEXSP_INVALID_ARGUMENT);
         CHECK(flexsp_attn_varlen_bwd(ctx, p, t, t, t, t, t, lse, nullptr, 0, 2, 0, 2, 1, 0.f, t, t, t, 7, nullptr) == FLEXSP_UNSUPPORTED);
         CHECK(flexsp_attn_varlen_fwd_kvshard(ctx, p, t, t, t, 0, 2, 0, 2, 1, 0.f, t, lse, nullptr) == FLEXSP_PLAN_MISMATCH);
+        CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, p, t, t, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_F32, 1, nullptr) == FLEXSP_PLAN_MISMATCH);
+        {
+            const int32_t cq[2] = {0, 8}, ck[2] = {0, 5}, sh[1] = {3};
+            flexsp_plan *sp = nullptr;
+            CHECK(flexsp_plan_create_kvshard(ctx, cq, ck, sh, 1, 2, 2, 64, 1, &sp) == FLEXSP_OK);
+            CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, sp, t, t, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_BF16, 1, nullptr) == FLEXSP_UNSUPPORTED);
+            CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, sp, t, t, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_F32, 2, nullptr) == FLEXSP_INVALID_ARGUMENT);
+            CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, sp, t, bad, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_F32, 1, nullptr) == FLEXSP_INVALID_ARGUMENT);
+            CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, sp, t, t, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_F32, 1, nullptr) == FLEXSP_NO_DEVICE);
+            flexsp_plan_destroy(sp);
+        }
         CHECK(flexsp_lse_merge(ctx, t, lse, t, lse, t, lse, 8, 2, 64, nullptr) == FLEXSP_NO_DEVICE);
         CHECK(flexsp_lse_merge(ctx, t, lse, t, lse, t, lse, 8, 2, 40, nullptr) == FLEXSP_UNSUPPORTED);
         CHECK(flexsp_pack(ctx, buf, buf + 2048, 4, 4, 8, 2, 2, nullptr) == FLEXSP_NO_DEVICE);

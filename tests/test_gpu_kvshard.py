@@ -124,6 +124,157 @@ def test_long_shard_tiles_cut_into_parts_and_merged(ctx, name, lq, lk, shift, Hq
         assert torch.equal(lse.view(torch.int32), runs[0][1].view(torch.int32)), "LSE is not reproducible"
 
 
+def _complete_statistics(q, k, v, cu_q, cu_k, shift, causal, extra, seed):
+    """(O, LSE, delta-free inputs) of a COMPLETE attention that the shard (k, v) is one part of: the other
+    part is `extra` more keys per sequence that every row sees (none if extra = 0).  Oracle only."""
+    O, LSE = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, shift, causal)
+    if extra:
+        B, Hkv, D = len(shift), k.shape[1], k.shape[2]
+        k2 = wl.normal_bf16(seed, 11, (extra * B, Hkv, D))
+        v2 = wl.normal_bf16(seed, 12, (extra * B, Hkv, D))
+        O2, L2 = oracle.attn_fwd_kvshard(q, k2, v2, cu_q, wl.cu_seqlens([extra] * B), [0] * B, False)
+        O, LSE = oracle.lse_merge(O, LSE, O2, L2)
+    return O, LSE
+
+
+def _shard_backward(ctx, q, k, v, o_bits, g, lse, cu_q, cu_k, shift, causal, grad_f32, accumulate_onto=None):
+    """HIP path: (dQ, dK, dV) as fp64 host arrays.  accumulate_onto: three fp32 host arrays to add to."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    Tq, Hq, D = q.shape
+    Tk, Hkv = k.shape[0], k.shape[1]
+    plan = fx.ShardPlan(ctx, cu_q, cu_k, shift, Hq, Hkv, D, causal)
+    kd = to_dev(k) if Tk else torch.zeros((8, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    vd = to_dev(v) if Tk else torch.zeros((8, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    gdt = torch.float32 if grad_f32 else torch.bfloat16
+    if accumulate_onto is None:
+        dq = torch.full((Tq, Hq, D), float("nan"), dtype=gdt, device="cuda")
+        dk = torch.full((max(Tk, 8), Hkv, D), float("nan"), dtype=gdt, device="cuda")
+        dv = torch.full((max(Tk, 8), Hkv, D), float("nan"), dtype=gdt, device="cuda")
+    else:
+        dq, dk, dv = (torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda() for x in accumulate_onto)
+    fx.flexsp_attn_varlen_bwd_kvshard(ctx, plan, to_dev(q), kd, vd, to_dev(o_bits), to_dev(g),
+                                      torch.from_numpy(np.ascontiguousarray(lse, dtype=np.float32)).cuda(), dq, dk, dv,
+                                      causal=causal, accumulate=accumulate_onto is not None)
+    torch.cuda.synchronize()
+    plan.close()
+    host = lambda t: t.cpu().numpy().astype(np.float64) if grad_f32 else bf16_f64(to_bits(t))
+    return host(dq), host(dk)[:Tk], host(dv)[:Tk]
+
+
+def _compare_grads(tag, got, ref, grad_f32, names=("dQ", "dK", "dV")):
+    for name, g_, r_ in zip(names, got, ref):
+        assert np.isfinite(g_).all(), f"{tag} {name}: non-finite values"
+        ma, rl = errors(g_, r_)
+        say(f"  {tag} {name}: max_abs={ma:.2e} rel_l2={rl:.2e}")
+        # (a gradient stored as bf16 carries its final rounding, up to 2^-8 of its value)
+        tol = MAX_ABS if grad_f32 else np.maximum(MAX_ABS, np.abs(r_) * 2.0 ** -8 + 1e-2)
+        assert (np.abs(g_ - r_) <= tol).all() and rl <= REL_L2, f"{tag} {name}"
+
+
+@pytest.mark.parametrize("extra", [0, 37], ids=["shard-is-everything", "one-part-of-more"])
+@pytest.mark.parametrize("name,lq,lk,shift,Hq,Hkv,D,causal", SHARD_CASES + CUT_CASES,
+                         ids=[c[0] for c in SHARD_CASES + CUT_CASES])
+def test_kvshard_backward_matches_oracle_elementwise(ctx, name, lq, lk, shift, Hq, Hkv, D, causal, extra):
+    """flexsp_attn_varlen_bwd_kvshard against the oracle's shard backward, every element of dQ (the shard's
+    part), dK and dV, fp32 and bf16 gradients.  The rows' log-sum-exp and output are those of a complete
+    attention of which the shard is the whole (extra = 0: rows without a visible key then have lse = -inf)
+    or one part (37 more keys per sequence that every row sees), computed by the oracle; the HIP path gets
+    the output rounded to bf16 and the log-sum-exp rounded to fp32, as the forward ring would leave them."""
+    say(f"key-shard backward {name}: queries {lq} keys {lk} shift {shift} Hq={Hq} Hkv={Hkv} D={D} causal={causal} extra={extra}")
+    seed = 5700 + len(name)
+    q = wl.normal_bf16(seed, wl.TID_Q, (sum(lq), Hq, D))
+    k = wl.normal_bf16(seed, wl.TID_K, (sum(lk), Hkv, D))
+    v = wl.normal_bf16(seed, wl.TID_V, (sum(lk), Hkv, D))
+    g = wl.normal_bf16(seed, wl.TID_DO, (sum(lq), Hq, D))
+    cu_q, cu_k = wl.cu_seqlens(lq), wl.cu_seqlens(lk)
+    O, LSE = _complete_statistics(q, k, v, cu_q, cu_k, shift, causal, extra, seed)
+    delta = np.einsum("thd,thd->ht", bf16_f64(g), O)
+    ref = oracle.attn_bwd_kvshard(q, k, v, g, LSE, delta, cu_q, cu_k, shift, causal)
+    o_bits = wl.f32_to_bf16_bits(O.astype(np.float32))
+    for grad_f32 in (True, False):
+        got = _shard_backward(ctx, q, k, v, o_bits, g, LSE, cu_q, cu_k, shift, causal, grad_f32)
+        _compare_grads(f"{name} {'fp32' if grad_f32 else 'bf16'}", got, ref, grad_f32)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_backward_ring_accumulates_into_the_full_backward(ctx, causal):
+    """One device's backward ring without the wire: it holds ALL query rows here (so dK / dV of a shard
+    are complete after its one visit), meets the keys in three shards, ADDS each shard's part of dQ into
+    one fp32 buffer and each shard's dK / dV onto a buffer that already holds numbers (what the previous
+    device of a ring would have left).  Against the oracle's full backward, and the forward ring's own
+    O / LSE feed the backward (nothing here comes from the oracle but the expected values)."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    lens, Hq, Hkv, D = [900, 64, 1, 333, 1500], 4, 2, 128
+    cu = wl.cu_seqlens(lens)
+    T, B = sum(lens), len(lens)
+    q = wl.normal_bf16(5800, wl.TID_Q, (T, Hq, D)); g = wl.normal_bf16(5800, wl.TID_DO, (T, Hq, D))
+    k = wl.normal_bf16(5800, wl.TID_K, (T, Hkv, D)); v = wl.normal_bf16(5800, wl.TID_V, (T, Hkv, D))
+    _, _, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, causal)
+    rng = np.random.default_rng(58)
+    c1 = [int(rng.integers(0, s + 1)) for s in lens]
+    c2 = [int(rng.integers(c, s + 1)) for c, s in zip(c1, lens)]
+    say(f"backward ring: lens={lens} key cuts {c1} {c2} causal={causal}")
+
+    def rows(x, lo, hi):
+        return np.concatenate([x[int(cu[b]) + lo[b]: int(cu[b]) + hi[b]] for b in range(B)])
+
+    shards = [([0] * B, c1), (c1, c2), (c2, list(lens))]
+    # forward ring: partial attentions folded in place
+    acc_o = acc_l = None
+    for lo, hi in shards:
+        o, lse = _shard_forward(ctx, q, rows(k, lo, hi), rows(v, lo, hi), cu, wl.cu_seqlens([h - l for l, h in zip(lo, hi)]),
+                                [-l for l in lo], causal)
+        if acc_o is None:
+            acc_o, acc_l = o, lse
+        else:
+            fx.flexsp_lse_merge(ctx, acc_o, acc_l, o, lse, acc_o, acc_l)
+    torch.cuda.synchronize()
+    o_bits, lse_host = to_bits(acc_o), acc_l.cpu().numpy()
+    # backward ring
+    dq_acc = np.zeros((T, Hq, D), dtype=np.float32)
+    for n, (lo, hi) in enumerate(shards):
+        ks, vs = rows(k, lo, hi), rows(v, lo, hi)
+        before_k = rng.standard_normal(ks.shape).astype(np.float32)
+        before_v = rng.standard_normal(vs.shape).astype(np.float32)
+        pad = lambda x: np.concatenate([x, np.zeros((max(8 - len(x), 0),) + x.shape[1:], dtype=np.float32)])
+        dq_new, dk_s, dv_s = _shard_backward(ctx, q, ks, vs, o_bits, g, lse_host, cu,
+                                             wl.cu_seqlens([h - l for l, h in zip(lo, hi)]), [-l for l in lo], causal,
+                                             True, accumulate_onto=(dq_acc, pad(before_k), pad(before_v)))
+        dq_acc = dq_new.astype(np.float32)
+        _compare_grads(f"ring shard {n}", (dk_s - before_k, dv_s - before_v), (rows(dK, lo, hi), rows(dV, lo, hi)), True,
+                       names=("dK", "dV"))
+    _compare_grads("ring", (dq_acc.astype(np.float64),), (dQ,), True, names=("dQ",))
+
+
+def test_kvshard_backward_error_paths(ctx):
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    Hq, Hkv, D = 2, 2, 128
+    sp = fx.ShardPlan(ctx, [0, 64], [0, 64], [0], Hq, Hkv, D, True)
+    op = fx.Plan(ctx, [0, 64], Hq, Hkv, D, True)
+    t = lambda h, dt=torch.bfloat16: torch.zeros((64, h, D), dtype=dt, device="cuda")
+    lse = torch.zeros((Hq, 64), dtype=torch.float32, device="cuda")
+    args = (t(Hq), t(Hkv), t(Hkv), t(Hq), t(Hq), lse)
+    with pytest.raises(fx.FlexspError) as e:      # partial sums are kept in fp32
+        fx.flexsp_attn_varlen_bwd_kvshard(ctx, sp, *args, t(Hq), t(Hkv), t(Hkv), accumulate=True)
+    assert e.value.status == fx.UNSUPPORTED
+    with pytest.raises(fx.FlexspError) as e:      # an ordinary plan does not serve the shard calls
+        fx.flexsp_attn_varlen_bwd_kvshard(ctx, op, *args, t(Hq), t(Hkv), t(Hkv))
+    assert e.value.status == fx.PLAN_MISMATCH
+    with pytest.raises(fx.FlexspError) as e:      # ... nor a shard plan the ordinary backward
+        fx.flexsp_attn_varlen_bwd(ctx, sp, *args, None, t(Hq), t(Hkv), t(Hkv))
+    assert e.value.status == fx.PLAN_MISMATCH
+    with pytest.raises(fx.FlexspError) as e:
+        fx.flexsp_attn_varlen_bwd_kvshard(ctx, sp, *args, t(Hq), t(Hkv), t(Hkv), causal=False)
+    assert e.value.status == fx.PLAN_MISMATCH
+    fx.flexsp_attn_varlen_bwd_kvshard(ctx, sp, *args, t(Hq, torch.float32), t(Hkv, torch.float32), t(Hkv, torch.float32),
+                                      accumulate=True)
+    torch.cuda.synchronize()
+    sp.close(); op.close()
+
+
 def test_aligned_shard_equals_the_ordinary_forward_bitwise(ctx):
     """shift = 0 and keys = the whole sequence is ordinary causal attention: same kernel arithmetic,
     so the key-shard call must reproduce flexsp_attn_varlen_fwd bit for bit."""

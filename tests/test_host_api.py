@@ -236,7 +236,15 @@ def test_kvshard_plan_lists_every_query_tile_and_validates(host_ctx):
     want = sorted((b, t, h) for b, s in enumerate(lq) for t in range((s + 127) // 128) for h in range(2))
     assert sorted(zip(items["seq_start"].tolist(), items["tile"].tolist(), items["head"].tolist())) == want
     assert all(lq[b] == n for b, n in zip(items["seq_start"], items["seq_len"]))
-    assert plan.num_items(fx.PASS_BWD_DKV) == 0 and plan.num_items(fx.PASS_BWD_DQ) == 0
+    # the dQ pass lists the same tiles; the dK/dV pass lists every (sequence with shard keys, 64-key tile of
+    # the shard, kv head)
+    dq_items, _ = plan.items(fx.PASS_BWD_DQ)
+    assert sorted(zip(dq_items["seq_start"].tolist(), dq_items["tile"].tolist(), dq_items["head"].tolist())) == want
+    dkv_items, _ = plan.items(fx.PASS_BWD_DKV)
+    want_k = sorted((b, t, 0) for b, s in enumerate(lk) for t in range((s + 63) // 64))
+    assert sorted(zip(dkv_items["seq_start"].tolist(), dkv_items["tile"].tolist(), dkv_items["head"].tolist())) == want_k
+    assert all(lk[b] == n for b, n in zip(dkv_items["seq_start"], dkv_items["seq_len"]))
+    assert (dkv_items["nparts"] == 1).all()
 
     def visible_tiles(b, t):
         keys = max(0, min(lk[b], (t + 1) * 128 + shift[b]))

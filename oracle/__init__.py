@@ -184,7 +184,6 @@ def attn_bwd_kvshard(q, k, v, dO, lse, delta, cu_q, cu_k, shift, causal=True, sc
     Visibility as in attn_fwd_kvshard.  Summed over the shards of a partition of the keys, the dQ parts give dQ
     of the complete attention, and each key's dK / dV are complete by themselves.  A row with lse = -inf (it
     saw no key anywhere) contributes nothing.  Returns (dQ_part [Tq,Hq,D], dK [Tk,Hkv,D], dV [Tk,Hkv,D]), fp64."""
-    q, _ = _in(q); k, _ = _in(k); v, _ = _in(v); dO, _ = _in(dO)
     q, k, v, dO = (bf16_or_f64(x) for x in (q, k, v, dO))
     lse = np.asarray(lse, dtype=np.float64); delta = np.asarray(delta, dtype=np.float64)
     Tq, Hq, D = q.shape

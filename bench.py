@@ -42,8 +42,8 @@ HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 # counter values and the algorithmic bytes beside them are in profiles/attention_hbm_traffic.md).
 # bench.py cannot run the profiler on itself: these are the figures of that summary.
 MEASURED_HBM_TRAFFIC = {
-    ("pareto-64k", "fwd"): 1312488723, ("pareto-64k", "bwd_dq"): 1539995098, ("pareto-64k", "bwd_dkv"): 1609902715,
-    ("single-128k", "fwd"): 12145695157, ("single-128k", "bwd_dq"): 28410988235, ("single-128k", "bwd_dkv"): 10205210938,
+    ("pareto-64k", "fwd"): 1312757476, ("pareto-64k", "bwd_dq"): 1520697294, ("pareto-64k", "bwd_dkv"): 1609165962,
+    ("single-128k", "fwd"): 11856153155, ("single-128k", "bwd_dq"): 25460015209, ("single-128k", "bwd_dkv"): 10277606411,
 }
 
 

@@ -261,8 +261,11 @@ void build_pass(const std::vector<int32_t> &cu, int B, int heads, int group_mult
 }
 
 // Cuts tiles that would outlast an even share of the pass into parts (see flexsp_item): with W =
-// total steps / workgroups, a tile of c steps becomes ceil(c / max(3W/4, kMinPartSteps)) parts of
-// equal length (at most kMaxParts, none shorter than kMinPartSteps).  Longest-first scheduling alone
+// total steps / workgroups, a tile of c steps becomes ceil(c / L) parts of equal length (at most
+// kMaxParts, none shorter than kMinPartSteps), where the part length aimed at is L = 3W/4 while that
+// is at most kLongPartSteps, then kLongPartSteps, and 0.35 W once that is longer still: a part costs
+// its hand-over (a few steps' time) whatever its length, so short parts are kept few and long ones
+// are made finer, which evens out the end of the pass.  Longest-first scheduling alone
 // finishes no earlier than the longest item, which for a batch of few heads and one dominant
 // sequence is several times the even share: the compute units that run out of work wait for it.
 // `spare`: tiles of up to this many even shares are left whole (0: every tile longer than a part is cut).
@@ -278,7 +281,8 @@ void split_long_items(std::vector<Work> &work, int n_wg, int spare, HostPass &ou
         total += w.cost;
     }
     const int64_t share = total / std::max(n_wg, 1);
-    const int64_t target = std::max<int64_t>(share * 3 / 4, kMinPartSteps);
+    const int64_t target = std::max<int64_t>(
+        std::min(share * 3 / 4, std::max<int64_t>(share * 35 / 100, kLongPartSteps)), kMinPartSteps);
     const size_t n0 = work.size();
     for (size_t i = 0; i < n0; i++) {
         const int64_t c = work[i].cost;

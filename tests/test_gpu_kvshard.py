@@ -248,6 +248,75 @@ def test_backward_ring_accumulates_into_the_full_backward(ctx, causal):
     _compare_grads("ring", (dq_acc.astype(np.float64),), (dQ,), True, names=("dQ",))
 
 
+def test_four_emulated_devices_ring_forward_and_backward_equal_the_unsplit_attention(ctx):
+    """Context parallelism over four devices, all played by the one GPU, without the wire: device r holds the
+    r-th quarter of every sequence's rows; in the forward every device meets every key shard (the ones that
+    lie after its rows give nothing) and merges; in the backward dq stays with its device and gathers the
+    shards' parts, dk / dv belong to a shard and gather the devices' parts (accumulate = 1 onto fp32
+    buffers that start at zero).  The pieces put together must be the oracle's attention over the unsplit
+    batch, forward and backward, at the stated tolerances."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    lens, Hq, Hkv, D, P = [6144, 2048, 333], 2, 1, 128, 4
+    cu = wl.cu_seqlens(lens)
+    T, B = sum(lens), len(lens)
+    q = wl.normal_bf16(5900, wl.TID_Q, (T, Hq, D)); g = wl.normal_bf16(5900, wl.TID_DO, (T, Hq, D))
+    k = wl.normal_bf16(5900, wl.TID_K, (T, Hkv, D)); v = wl.normal_bf16(5900, wl.TID_V, (T, Hkv, D))
+    O, LSE, dQ, dK, dV = oracle.attn_fwd_bwd(q, k, v, g, cu, True)
+    cut = [[(j * s) // P for j in range(P + 1)] for s in lens]
+    say(f"four devices: lens={lens} cuts={cut}")
+
+    def rows(x, j):
+        return np.concatenate([x[int(cu[b]) + c[j]: int(cu[b]) + c[j + 1]] for b, c in enumerate(cut)])
+
+    def scatter(parts):   # per-device row blocks -> the packed order
+        out = np.zeros((T,) + parts[0].shape[1:], dtype=parts[0].dtype)
+        for j, x in enumerate(parts):
+            at = 0
+            for b, c in enumerate(cut):
+                n = c[j + 1] - c[j]
+                out[int(cu[b]) + c[j]: int(cu[b]) + c[j + 1]] = x[at: at + n]
+                at += n
+        return out
+
+    cu_part = [wl.cu_seqlens([c[j + 1] - c[j] for c in cut]) for j in range(P)]
+    kd = [to_dev(rows(k, j)) for j in range(P)]
+    vd = [to_dev(rows(v, j)) for j in range(P)]
+    dk = [torch.zeros(kd[j].shape, dtype=torch.float32, device="cuda") for j in range(P)]
+    dv = [torch.zeros(vd[j].shape, dtype=torch.float32, device="cuda") for j in range(P)]
+    o_parts, l_parts, dq_parts = [], [], []
+    for r in range(P):                                   # device r
+        qd, gd = to_dev(rows(q, r)), to_dev(rows(g, r))
+        Tq = qd.shape[0]
+        plans = [fx.ShardPlan(ctx, cu_part[r], cu_part[j], [c[r] - c[j] for c in cut], Hq, Hkv, D, True) for j in range(P)]
+        o_acc = torch.empty((Tq, Hq, D), dtype=torch.bfloat16, device="cuda")
+        l_acc = torch.empty((Hq, Tq), dtype=torch.float32, device="cuda")
+        o_new, l_new = torch.empty_like(o_acc), torch.empty_like(l_acc)
+        for n, j in enumerate([(r - i) % P for i in range(P)]):      # its own shard first, then round the ring
+            o, l = (o_acc, l_acc) if n == 0 else (o_new, l_new)
+            fx.flexsp_attn_varlen_fwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o, l)
+            if n:
+                fx.flexsp_lse_merge(ctx, o_acc, l_acc, o_new, l_new, o_acc, l_acc)
+        dq = torch.zeros((Tq, Hq, D), dtype=torch.float32, device="cuda")
+        for j in [(r - i) % P for i in range(P)]:
+            fx.flexsp_attn_varlen_bwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o_acc, gd, l_acc, dq, dk[j], dv[j],
+                                              accumulate=True)
+        torch.cuda.synchronize()
+        for pl in plans:
+            pl.close()
+        o_parts.append(bf16_f64(to_bits(o_acc)))
+        l_parts.append(l_acc.cpu().numpy().astype(np.float64).T.copy())      # [Tq, Hq] for scatter()
+        dq_parts.append(dq.cpu().numpy().astype(np.float64))
+    got_o, got_l, got_dq = scatter(o_parts), scatter(l_parts).T, scatter(dq_parts)
+    got_dk = scatter([x.cpu().numpy().astype(np.float64) for x in dk])
+    got_dv = scatter([x.cpu().numpy().astype(np.float64) for x in dv])
+    ma, rl = errors(got_o, O)
+    el = float(np.abs(got_l - LSE).max())
+    say(f"  ring of four: O max_abs={ma:.2e} rel_l2={rl:.2e} LSE max_abs={el:.2e}")
+    assert ma <= MAX_ABS and rl <= REL_L2 and el < 1e-3
+    _compare_grads("ring of four", (got_dq, got_dk, got_dv), (dQ, dK, dV), True)
+
+
 def test_kvshard_backward_error_paths(ctx):
     import torch
     from paper_2412_01523_amd import binding as fx

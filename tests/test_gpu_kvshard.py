@@ -248,6 +248,47 @@ def test_backward_ring_accumulates_into_the_full_backward(ctx, causal):
     _compare_grads("ring", (dq_acc.astype(np.float64),), (dQ,), True, names=("dQ",))
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shard_configs_forward_and_backward(ctx, seed):
+    """Random sequence counts, query and key lengths (empty ones included), shifts on both sides of the
+    diagonal, head counts, head dims and causality, forward and backward against the oracle.  A shard of a
+    few keys that hundreds of rows see collects gradients far beyond the N(0,1) magnitudes the stated
+    max-abs bound belongs to: there the bound scales with the tensor's largest value (relative L2 as stated)."""
+    rng = np.random.default_rng(6100 + seed)
+
+    def rlen():
+        kind = rng.integers(0, 8)
+        return 0 if kind == 0 else int(rng.integers(1, 5)) if kind == 1 else int(rng.integers(1, 300)) if kind <= 4 \
+            else int(rng.integers(300, 2500))
+
+    B = int(rng.integers(1, 6)); Hkv = int(rng.integers(1, 3)); Hq = Hkv * int(rng.choice([1, 2, 4]))
+    D = int(rng.choice([64, 128])); causal = bool(rng.integers(0, 4) != 0)
+    lq, lk = [rlen() for _ in range(B)], [rlen() for _ in range(B)]
+    if sum(lq) == 0:
+        lq[0] = 7
+    shift = [int(rng.integers(-300, 3000)) if rng.integers(0, 3) else int(rng.integers(-40, 40)) for _ in range(B)]
+    extra = int(rng.choice([0, 21]))
+    say(f"random shard case {seed}: queries {lq} keys {lk} shift {shift} Hq={Hq} Hkv={Hkv} D={D} causal={causal} extra={extra}")
+    q = wl.normal_bf16(6100 + seed, wl.TID_Q, (sum(lq), Hq, D)); g = wl.normal_bf16(6100 + seed, wl.TID_DO, (sum(lq), Hq, D))
+    k = wl.normal_bf16(6100 + seed, wl.TID_K, (sum(lk), Hkv, D)); v = wl.normal_bf16(6100 + seed, wl.TID_V, (sum(lk), Hkv, D))
+    cu_q, cu_k = wl.cu_seqlens(lq), wl.cu_seqlens(lk)
+    O1, L1 = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, shift, causal)
+    o, lse = _shard_forward(ctx, q, k, v, cu_q, cu_k, shift, causal)
+    _compare(f"random {seed}", o, lse, O1, L1)
+    O, LSE = _complete_statistics(q, k, v, cu_q, cu_k, shift, causal, extra, 6100 + seed)
+    delta = np.einsum("thd,thd->ht", bf16_f64(g), O)
+    ref = oracle.attn_bwd_kvshard(q, k, v, g, LSE, delta, cu_q, cu_k, shift, causal)
+    o_bits = wl.f32_to_bf16_bits(O.astype(np.float32))
+    for grad_f32 in (True, False):
+        got = _shard_backward(ctx, q, k, v, o_bits, g, LSE, cu_q, cu_k, shift, causal, grad_f32)
+        for name, g_, r_ in zip(("dQ", "dK", "dV"), got, ref):
+            assert np.isfinite(g_).all(), f"{name}: non-finite values"
+            ma, rl = errors(g_, r_)
+            big = max(1.0, float(np.abs(r_).max(initial=0.0)) / 4.0)
+            say(f"  random {seed} {name} {'fp32' if grad_f32 else 'bf16'}: max_abs={ma:.2e} rel_l2={rl:.2e} (largest value {np.abs(r_).max(initial=0.0):.1f})")
+            assert ma <= (MAX_ABS if grad_f32 else 2 * MAX_ABS) * big and rl <= REL_L2, name
+
+
 def test_four_emulated_devices_ring_forward_and_backward_equal_the_unsplit_attention(ctx):
     """Context parallelism over four devices, all played by the one GPU, without the wire: device r holds the
     r-th quarter of every sequence's rows; in the forward every device meets every key shard (the ones that

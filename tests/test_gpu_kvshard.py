@@ -167,8 +167,8 @@ def _compare_grads(tag, got, ref, grad_f32, names=("dQ", "dK", "dV")):
         assert np.isfinite(g_).all(), f"{tag} {name}: non-finite values"
         ma, rl = errors(g_, r_)
         say(f"  {tag} {name}: max_abs={ma:.2e} rel_l2={rl:.2e}")
-        # (a gradient stored as bf16 carries its final rounding, up to 2^-8 of its value)
-        tol = MAX_ABS if grad_f32 else np.maximum(MAX_ABS, np.abs(r_) * 2.0 ** -8 + 1e-2)
+        # (a gradient stored as bf16 carries its final rounding on top, up to 2^-8 of its value)
+        tol = MAX_ABS if grad_f32 else MAX_ABS + np.abs(r_) * 2.0 ** -8
         assert (np.abs(g_ - r_) <= tol).all() and rl <= REL_L2, f"{tag} {name}"
 
 
@@ -253,7 +253,9 @@ def test_random_shard_configs_forward_and_backward(ctx, seed):
     """Random sequence counts, query and key lengths (empty ones included), shifts on both sides of the
     diagonal, head counts, head dims and causality, forward and backward against the oracle.  A shard of a
     few keys that hundreds of rows see collects gradients far beyond the N(0,1) magnitudes the stated
-    max-abs bound belongs to: there the bound scales with the tensor's largest value (relative L2 as stated)."""
+    max-abs bound belongs to (2e-2 on values up to about 4): there the bound is the same fraction, 5e-3, of
+    the tensor's largest value, i.e. max-abs <= max(2e-2, 5e-3 max|ref|), plus the final rounding (2^-8 of
+    the value) for gradients stored as bf16; relative L2 as stated."""
     rng = np.random.default_rng(6100 + seed)
 
     def rlen():
@@ -284,9 +286,10 @@ def test_random_shard_configs_forward_and_backward(ctx, seed):
         for name, g_, r_ in zip(("dQ", "dK", "dV"), got, ref):
             assert np.isfinite(g_).all(), f"{name}: non-finite values"
             ma, rl = errors(g_, r_)
-            big = max(1.0, float(np.abs(r_).max(initial=0.0)) / 4.0)
-            say(f"  random {seed} {name} {'fp32' if grad_f32 else 'bf16'}: max_abs={ma:.2e} rel_l2={rl:.2e} (largest value {np.abs(r_).max(initial=0.0):.1f})")
-            assert ma <= (MAX_ABS if grad_f32 else 2 * MAX_ABS) * big and rl <= REL_L2, name
+            top = float(np.abs(r_).max(initial=0.0))
+            tol = max(MAX_ABS, REL_L2 * top) + (0.0 if grad_f32 else np.abs(r_) * 2.0 ** -8)
+            say(f"  random {seed} {name} {'fp32' if grad_f32 else 'bf16'}: max_abs={ma:.2e} rel_l2={rl:.2e} (largest value {top:.1f})")
+            assert (np.abs(g_ - r_) <= tol).all() and rl <= REL_L2, name
 
 
 def test_four_emulated_devices_ring_forward_and_backward_equal_the_unsplit_attention(ctx):

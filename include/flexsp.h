@@ -284,6 +284,15 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
  *   whatever its O holds; both -inf: O = 0, LSE = -inf.  o_out / lse_out may be the very same memory as
  *   one of the inputs (merge in place), but must not overlap them otherwise.  Merging is associative up
  *   to rounding, so shards can be folded in as they arrive.
+ *
+ * flexsp_lse_merge_acc - the same merge with the running result kept in fp32, for rings of many shards
+ *   (folding P parts into a bf16 result rounds it P - 1 times; here only `o_bf16` is rounded, once):
+ *   (o_acc, lse_acc) <- merge((o_acc, lse_acc), (o_b, lse_b)) in place.  o_acc is a view of [T, H, D] FP32
+ *   (strides in fp32 elements, rows 16-byte aligned), lse_acc fp32 [H, T]; o_b a bf16 view, lse_b fp32
+ *   [H, T].  Start a ring with lse_acc = -inf everywhere (o_acc may then hold anything: a part with
+ *   LSE = -inf counts nothing).  If o_bf16.ptr is not NULL the merged rows are also written there rounded
+ *   to bf16 (a view of [T, H, D] bf16: what flexsp_attn_varlen_bwd_kvshard takes as `o`); pass it on the
+ *   last fold, or on every one.
  * Errors: INVALID_ARGUMENT, UNSUPPORTED, PLAN_MISMATCH, NO_DEVICE, OUT_OF_MEMORY, HIP_ERROR.
  */
 int flexsp_plan_create_kvshard(flexsp_ctx *ctx, const int32_t *cu_q_host, const int32_t *cu_k_host,
@@ -301,6 +310,8 @@ int flexsp_attn_varlen_bwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_te
                                    flexsp_stream stream);
 int flexsp_lse_merge(flexsp_ctx *ctx, flexsp_tensor o_a, const float *lse_a, flexsp_tensor o_b, const float *lse_b,
                      flexsp_tensor o_out, float *lse_out, int64_t T, int32_t H, int32_t D, flexsp_stream stream);
+int flexsp_lse_merge_acc(flexsp_ctx *ctx, flexsp_tensor o_acc, float *lse_acc, flexsp_tensor o_b, const float *lse_b,
+                         flexsp_tensor o_bf16, int64_t T, int32_t H, int32_t D, flexsp_stream stream);
 
 /*
  * The forward for callers that cannot allocate: code under HIP graph capture, tight serving loops,

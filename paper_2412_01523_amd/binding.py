@@ -26,7 +26,7 @@ EXPORTS = (
     "flexsp_plan_tile_rows", "flexsp_attn_bwd_workspace_bytes",
     "flexsp_pack", "flexsp_unpack", "flexsp_pack_many", "flexsp_unpack_many",
     "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd", "flexsp_attn_varlen_fwd_static",
-    "flexsp_plan_create_kvshard", "flexsp_attn_varlen_fwd_kvshard", "flexsp_attn_varlen_bwd_kvshard", "flexsp_lse_merge",
+    "flexsp_plan_create_kvshard", "flexsp_attn_varlen_fwd_kvshard", "flexsp_attn_varlen_bwd_kvshard", "flexsp_lse_merge", "flexsp_lse_merge_acc",
     "flexsp_profile_start", "flexsp_profile_stop",
     "flexsp_bucket_dp", "flexsp_chunk_dp", "flexsp_min_microbatches",
 )
@@ -114,6 +114,8 @@ def lib() -> ctypes.CDLL:
                                                      Tensor, c_int32, c_int32, c_void_p]
         L.flexsp_lse_merge.argtypes = [c_void_p, Tensor, c_void_p, Tensor, c_void_p, Tensor, c_void_p, c_int64,
                                        c_int32, c_int32, c_void_p]
+        L.flexsp_lse_merge_acc.argtypes = [c_void_p, Tensor, c_void_p, Tensor, c_void_p, Tensor, c_int64, c_int32, c_int32,
+                                           c_void_p]
         L.flexsp_bucket_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int32), c_void_p,
                                        POINTER(c_int64)]
         L.flexsp_chunk_dp.argtypes = [c_void_p, c_int64, c_int32, c_void_p, POINTER(c_int64)]
@@ -355,6 +357,19 @@ def flexsp_lse_merge(ctx: Context, o_a, lse_a, o_b, lse_b, o_out, lse_out, strea
     assert lse_a.is_contiguous() and lse_b.is_contiguous() and lse_out.is_contiguous()
     _check(lib().flexsp_lse_merge(ctx.handle, _view(o_a), lse_a.data_ptr(), _view(o_b), lse_b.data_ptr(), _view(o_out),
                                   lse_out.data_ptr(), T, H, D, _stream(stream)), "flexsp_lse_merge")
+
+
+def flexsp_lse_merge_acc(ctx: Context, o_acc, lse_acc, o_b, lse_b, o_bf16=None, stream=None):
+    """o_acc [T,H,D] fp32 view and lse_acc [H,T] fp32: the running result, updated in place; o_b bf16 view, lse_b
+    [H,T] fp32: the new part; o_bf16: optional bf16 [T,H,D] view that receives the merged rows rounded once."""
+    import torch
+    T, H, D = o_acc.shape
+    assert o_acc.dtype == torch.float32 and o_b.shape == o_acc.shape and lse_acc.shape == lse_b.shape == (H, T)
+    assert lse_acc.is_contiguous() and lse_b.is_contiguous()
+    none = Tensor(None, 0, 0)
+    _check(lib().flexsp_lse_merge_acc(ctx.handle, _view(o_acc), lse_acc.data_ptr(), _view(o_b), lse_b.data_ptr(),
+                                      none if o_bf16 is None else _view(o_bf16), T, H, D, _stream(stream)),
+           "flexsp_lse_merge_acc")
 
 
 def flexsp_attn_varlen_fwd_static(ctx: Context, q, k, v, cu_seqlens_dev, o, lse, *, head_begin=0, head_count=None,

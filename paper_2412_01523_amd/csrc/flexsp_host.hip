@@ -1114,6 +1114,24 @@ int flexsp_lse_merge(flexsp_ctx *ctx, flexsp_tensor o_a, const float *lse_a, fle
     return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
 }
 
+int flexsp_lse_merge_acc(flexsp_ctx *ctx, flexsp_tensor o_acc, float *lse_acc, flexsp_tensor o_b, const float *lse_b,
+                         flexsp_tensor o_bf16, int64_t T, int32_t H, int32_t D, flexsp_stream stream)
+{
+    if (!ctx || T < 0 || H <= 0 || D <= 0) return FLEXSP_INVALID_ARGUMENT;
+    if (D != 64 && D != 128) return FLEXSP_UNSUPPORTED;
+    if (T == 0) return FLEXSP_OK;
+    if (!view_ok(o_acc) || !view_ok(o_b) || (o_bf16.ptr && !view_ok(o_bf16)) || !lse_acc || !lse_b)
+        return FLEXSP_INVALID_ARGUMENT;
+    if (T * (int64_t)H * (D / 8) >= ((int64_t)1 << 31)) return FLEXSP_UNSUPPORTED;
+    if (ctx->device < 0) return FLEXSP_NO_DEVICE;
+    hipError_t e = launch_lse_merge_acc((float *)o_acc.ptr, lse_acc, (const uint16_t *)o_b.ptr, lse_b, (uint16_t *)o_bf16.ptr,
+                                        T, H, D, (int32_t)o_acc.stride_token, (int32_t)o_acc.stride_head,
+                                        (int32_t)o_b.stride_token, (int32_t)o_b.stride_head,
+                                        o_bf16.ptr ? (int32_t)o_bf16.stride_token : 0,
+                                        o_bf16.ptr ? (int32_t)o_bf16.stride_head : 0, (hipStream_t)stream);
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
 int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
                            flexsp_tensor v, flexsp_tensor o, flexsp_tensor dO, const float *lse,
                            const int32_t *cu_dev, int32_t head_begin, int32_t head_count,

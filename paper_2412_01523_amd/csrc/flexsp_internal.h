@@ -85,6 +85,9 @@ hipError_t launch_attn_fwd_kvshard(const AttnArgs &a, int D, int grid, hipStream
 hipError_t launch_lse_merge(const uint16_t *oa, const float *la, const uint16_t *ob, const float *lb, uint16_t *oo,
                             float *lo, int64_t T, int H, int D, int32_t oa_st, int32_t oa_sh, int32_t ob_st,
                             int32_t ob_sh, int32_t oo_st, int32_t oo_sh, hipStream_t s);
+hipError_t launch_lse_merge_acc(float *oacc, float *lacc, const uint16_t *ob, const float *lb, uint16_t *ob16, int64_t T,
+                                int H, int D, int32_t oa_st, int32_t oa_sh, int32_t ob_st, int32_t ob_sh, int32_t o16_st,
+                                int32_t o16_sh, hipStream_t s);
 hipError_t launch_attn_bwd_dkv(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dq(const AttnArgs &a, int D, int grid, hipStream_t s);
 hipError_t launch_attn_bwd_dkv_kvshard(const AttnArgs &a, int D, int grid, hipStream_t s);  // a.pq.items: flexsp_shard_item;

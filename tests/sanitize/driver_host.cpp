@@ -22,6 +22,8 @@ hipError_t launch_attn_bwd_dkv_kvshard(const AttnArgs &, int, int, hipStream_t) 
 hipError_t launch_attn_bwd_dq_kvshard(const AttnArgs &, int, int, hipStream_t) { return hipErrorUnknown; }
 hipError_t launch_lse_merge(const uint16_t *, const float *, const uint16_t *, const float *, uint16_t *, float *, int64_t,
                             int, int, int32_t, int32_t, int32_t, int32_t, int32_t, int32_t, hipStream_t) { return hipErrorUnknown; }
+hipError_t launch_lse_merge_acc(float *, float *, const uint16_t *, const float *, uint16_t *, int64_t, int, int, int32_t,
+                                int32_t, int32_t, int32_t, int32_t, int32_t, hipStream_t) { return hipErrorUnknown; }
 hipError_t static_scratch_init(int) { return hipErrorUnknown; }
 }  // namespace flexsp
 
@@ -94,6 +96,9 @@ int main()
         }
         CHECK(flexsp_lse_merge(ctx, t, lse, t, lse, t, lse, 8, 2, 64, nullptr) == FLEXSP_NO_DEVICE);
         CHECK(flexsp_lse_merge(ctx, t, lse, t, lse, t, lse, 8, 2, 40, nullptr) == FLEXSP_UNSUPPORTED);
+        CHECK(flexsp_lse_merge_acc(ctx, t, lse, t, lse, flexsp_tensor{nullptr, 0, 0}, 8, 2, 64, nullptr) == FLEXSP_NO_DEVICE);
+        CHECK(flexsp_lse_merge_acc(ctx, t, lse, t, lse, bad, 8, 2, 64, nullptr) == FLEXSP_INVALID_ARGUMENT);
+        CHECK(flexsp_lse_merge_acc(ctx, t, nullptr, t, lse, t, 8, 2, 64, nullptr) == FLEXSP_INVALID_ARGUMENT);
         CHECK(flexsp_pack(ctx, buf, buf + 2048, 4, 4, 8, 2, 2, nullptr) == FLEXSP_NO_DEVICE);
         CHECK(flexsp_pack(ctx, buf, buf + 100, 4, 4, 8, 2, 2, nullptr) == FLEXSP_INVALID_ARGUMENT);
         flexsp_plan_destroy(p);

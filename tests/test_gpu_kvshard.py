@@ -333,14 +333,14 @@ def test_four_emulated_devices_ring_forward_and_backward_equal_the_unsplit_atten
         qd, gd = to_dev(rows(q, r)), to_dev(rows(g, r))
         Tq = qd.shape[0]
         plans = [fx.ShardPlan(ctx, cu_part[r], cu_part[j], [c[r] - c[j] for c in cut], Hq, Hkv, D, True) for j in range(P)]
-        o_acc = torch.empty((Tq, Hq, D), dtype=torch.bfloat16, device="cuda")
-        l_acc = torch.empty((Hq, Tq), dtype=torch.float32, device="cuda")
-        o_new, l_new = torch.empty_like(o_acc), torch.empty_like(l_acc)
-        for n, j in enumerate([(r - i) % P for i in range(P)]):      # its own shard first, then round the ring
-            o, l = (o_acc, l_acc) if n == 0 else (o_new, l_new)
-            fx.flexsp_attn_varlen_fwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o, l)
-            if n:
-                fx.flexsp_lse_merge(ctx, o_acc, l_acc, o_new, l_new, o_acc, l_acc)
+        o_acc = torch.empty((Tq, Hq, D), dtype=torch.bfloat16, device="cuda")       # the complete O, rounded once
+        o_run = torch.empty((Tq, Hq, D), dtype=torch.float32, device="cuda")        # the running result
+        l_acc = torch.full((Hq, Tq), float("-inf"), dtype=torch.float32, device="cuda")
+        o_new = torch.empty_like(o_acc)
+        l_new = torch.empty((Hq, Tq), dtype=torch.float32, device="cuda")
+        for j in [(r - i) % P for i in range(P)]:                    # its own shard first, then round the ring
+            fx.flexsp_attn_varlen_fwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o_new, l_new)
+            fx.flexsp_lse_merge_acc(ctx, o_run, l_acc, o_new, l_new, o_acc)
         dq = torch.zeros((Tq, Hq, D), dtype=torch.float32, device="cuda")
         for j in [(r - i) % P for i in range(P)]:
             fx.flexsp_attn_varlen_bwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o_acc, gd, l_acc, dq, dk[j], dv[j],
@@ -489,6 +489,51 @@ def test_lse_merge_matches_oracle_and_ignores_parts_without_keys(ctx):
         assert torch.equal(la_d, lo) and not wide[:, 0].any() and not wide[:, H + 1].any()
 
 
+def test_lse_merge_acc_keeps_the_running_result_in_fp32(ctx):
+    """flexsp_lse_merge_acc against the oracle's merge: the fp32 running result to fp32 accuracy, the optional
+    bf16 copy = that result rounded once (bit for bit), a ring started from lse = -inf over rubbish, and the
+    reason it exists: sixteen parts folded one by one stay at fp32 accuracy, where the bf16 merge has
+    rounded the running result fifteen times."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    T, H, D = 300, 3, 128
+    rng = np.random.default_rng(77)
+    acc = rng.standard_normal((T, H, D)).astype(np.float32)
+    ob = wl.normal_bf16(5510, 1, (T, H, D))
+    la = rng.normal(3.0, 2.0, (H, T)).astype(np.float32); lb = rng.normal(3.0, 2.0, (H, T)).astype(np.float32)
+    la[0, ::7] = -np.inf; lb[0, ::5] = -np.inf
+    O, L = oracle.lse_merge(acc.astype(np.float64), la, bf16_f64(ob), lb)
+    acc_d = torch.from_numpy(acc).cuda()
+    acc_d[::7, 0] = float("nan")                  # whatever a part without keys holds must not leak
+    la_d, lb_d = torch.from_numpy(la).cuda(), torch.from_numpy(lb).cuda()
+    o16 = torch.full((T, H, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    fx.flexsp_lse_merge_acc(ctx, acc_d, la_d, to_dev(ob), lb_d, o16)
+    torch.cuda.synchronize()
+    got, gl = acc_d.cpu().numpy().astype(np.float64), la_d.cpu().numpy().astype(np.float64)
+    dead = np.isneginf(L)
+    assert np.isfinite(got).all() and (np.isneginf(gl) == dead).all() and not got[dead.T].any()
+    assert np.abs(got - O).max() <= 1e-5 and np.abs(gl[~dead] - L[~dead]).max() <= 1e-5
+    assert torch.equal(o16.view(torch.int16), acc_d.to(torch.bfloat16).view(torch.int16))
+    # sixteen parts, one by one
+    parts = [(wl.normal_bf16(5520 + n, 0, (T, H, D)), rng.normal(0.0, 1.0, (H, T)).astype(np.float32)) for n in range(16)]
+    Or, Lr = bf16_f64(parts[0][0]), parts[0][1].astype(np.float64)
+    for o_n, l_n in parts[1:]:
+        Or, Lr = oracle.lse_merge(Or, Lr, bf16_f64(o_n), l_n)
+    acc_d = torch.full((T, H, D), float("nan"), dtype=torch.float32, device="cuda")
+    lacc_d = torch.full((H, T), float("-inf"), dtype=torch.float32, device="cuda")
+    run16, lrun = to_dev(parts[0][0]).clone(), torch.from_numpy(parts[0][1]).cuda()
+    for n, (o_n, l_n) in enumerate(parts):
+        fx.flexsp_lse_merge_acc(ctx, acc_d, lacc_d, to_dev(o_n), torch.from_numpy(l_n).cuda())
+        if n:
+            fx.flexsp_lse_merge(ctx, run16, lrun, to_dev(o_n), torch.from_numpy(l_n).cuda(), run16, lrun)
+    torch.cuda.synchronize()
+    e32 = errors(acc_d.cpu().numpy().astype(np.float64), Or)
+    e16 = errors(bf16_f64(to_bits(run16)), Or)
+    say(f"  sixteen parts folded: fp32 running result rel_l2={e32[1]:.2e}, bf16 running result rel_l2={e16[1]:.2e}")
+    assert e32[1] <= 1e-5 and e16[1] <= REL_L2 and e32[1] < e16[1] / 50
+    assert np.abs(lacc_d.cpu().numpy() - Lr).max() <= 1e-5
+
+
 def test_kvshard_error_paths(ctx):
     import torch
     from paper_2412_01523_amd import binding as fx
@@ -507,3 +552,81 @@ def test_kvshard_error_paths(ctx):
         fx.flexsp_attn_varlen_bwd(ctx, shard, t, t, t, t, t, lse, None, t, t, t)
     assert e.value.status == fx.PLAN_MISMATCH
     shard.close(); plain.close()
+
+
+def test_ring_at_bench_size_sampled_against_the_oracle(ctx):
+    """The configuration `bench.py --kvshard-ring` times: the 131 072-token sequence (8 heads, D = 128) over a
+    ring of 8, the device with the last 16 384 query rows, forward ring (8 shard forwards folded into an fp32
+    running result) and
+    backward ring (8 shard backwards, fp32 accumulation).  The oracle cannot run that in full inside a test;
+    compared are outputs it computes one by one on the unsplit sequence: sampled rows of O, LSE and dQ (complete
+    after the last shard), and late rows of dK / dV of the device's OWN shard, whose keys no other device's
+    rows see, so that this device's part is the complete gradient.  Plus, over whole tensors: the ring's O rows
+    against the ordinary forward's on the unsplit sequence (HIP against HIP, within the parts' roundings)."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    cfg = next(c for c in wl.CONFIGS if c.name == "single-128k")
+    S, Hq, Hkv, D, P = cfg.tokens, cfg.hq, cfg.hkv, cfg.d, 8
+    C = S // P
+    say(f"ring at bench size: S={S} Hq={Hq} D={D} P={P}; generating inputs")
+    q, k, v, g = wl.make_qkvdo(cfg)
+    cu = wl.cu_seqlens([S])
+    first = S - C
+    qd, gd = to_dev(q[first:]), to_dev(g[first:])
+    kd, vd = to_dev(k), to_dev(v)
+    plans = [fx.ShardPlan(ctx, [0, C], [0, C], [first - j * C], Hq, Hkv, D, True) for j in range(P)]
+    o_acc = torch.empty((C, Hq, D), dtype=torch.bfloat16, device="cuda")            # the complete O, rounded once
+    o_run = torch.empty((C, Hq, D), dtype=torch.float32, device="cuda")             # the running result
+    l_acc = torch.full((Hq, C), float("-inf"), dtype=torch.float32, device="cuda")
+    o_new = torch.empty_like(o_acc)
+    l_new = torch.empty((Hq, C), dtype=torch.float32, device="cuda")
+    order = list(range(P - 1, -1, -1))
+    for j in order:
+        fx.flexsp_attn_varlen_fwd_kvshard(ctx, plans[j], qd, kd[j * C:(j + 1) * C], vd[j * C:(j + 1) * C], o_new, l_new)
+        fx.flexsp_lse_merge_acc(ctx, o_run, l_acc, o_new, l_new, o_acc)
+    dq = torch.zeros((C, Hq, D), dtype=torch.float32, device="cuda")
+    dk_own = torch.zeros((C, Hkv, D), dtype=torch.float32, device="cuda")
+    dv_own = torch.zeros((C, Hkv, D), dtype=torch.float32, device="cuda")
+    dk_other, dv_other = torch.zeros_like(dk_own), torch.zeros_like(dv_own)
+    for j in order:
+        own = j == P - 1
+        fx.flexsp_attn_varlen_bwd_kvshard(ctx, plans[j], qd, kd[j * C:(j + 1) * C], vd[j * C:(j + 1) * C], o_acc, gd, l_acc,
+                                          dq, dk_own if own else dk_other, dv_own if own else dv_other, accumulate=True)
+    torch.cuda.synchronize()
+    for pl in plans:
+        pl.close()
+    assert torch.isfinite(dq).all() and torch.isfinite(dk_own).all() and torch.isfinite(dv_own).all()
+    say("  HIP rings done; sampling the oracle")
+    rng = np.random.Generator(np.random.Philox(key=[cfg.seed, 777]))
+    rows = sorted(set([0, 1, 31, 32, 127, 128, C // 2, C - 129, C - 2, C - 1] + [int(x) for x in rng.integers(0, C, size=14)]))
+    tok = np.array([first + r for r in rows], dtype=np.int64)
+    head = rng.integers(0, Hq, size=len(tok)).astype(np.int32)
+    Or, Lr, dQr = oracle.rows(q, k, v, g, cu, tok, head, True)
+    rr, hh = torch.from_numpy(np.array(rows)).cuda(), torch.from_numpy(head.astype(np.int64)).cuda()
+    Og = bf16_f64(to_bits(o_acc[rr, hh])); Lg = l_acc[hh, rr].cpu().numpy().astype(np.float64)
+    dQg = dq[rr, hh].cpu().numpy().astype(np.float64)
+    eo, eq = errors(Og, Or), errors(dQg, dQr)
+    say(f"  {len(tok)} sampled rows: O (max_abs, rel_l2)=({eo[0]:.2e},{eo[1]:.2e}) dQ=({eq[0]:.2e},{eq[1]:.2e}) LSE max_abs={np.abs(Lg - Lr).max():.2e}")
+    assert eo[0] <= MAX_ABS and eo[1] <= REL_L2 and eq[0] <= MAX_ABS and eq[1] <= REL_L2 and np.abs(Lg - Lr).max() < 1e-3
+    # dK / dV of the own shard: keys first .. S-1, seen by this device's rows only
+    # (the oracle needs the complete softmax row of every query that sees a sampled key: keys of the last
+    # 1 500 positions, two heads; deeper accumulation is compared at sizes the oracle runs in full, above)
+    keys, kv_heads = [C - 1500, C - 701, C - 65, C - 64, C - 1], sorted({0, Hkv - 1})
+    dKr, dVr = oracle.dkv_rows(q, k, v, g, cu, [(0, gk, [first + j for j in keys]) for gk in kv_heads], True)
+    kk = torch.from_numpy(np.array(keys)).cuda()
+    dKg = torch.cat([dk_own[kk, gk] for gk in kv_heads]).cpu().numpy().astype(np.float64)
+    dVg = torch.cat([dv_own[kk, gk] for gk in kv_heads]).cpu().numpy().astype(np.float64)
+    ek, ev = errors(dKg, dKr), errors(dVg, dVr)
+    say(f"  {len(keys)} x {len(kv_heads)} own-shard key rows: dK=({ek[0]:.2e},{ek[1]:.2e}) dV=({ev[0]:.2e},{ev[1]:.2e})")
+    assert ek[0] <= MAX_ABS and ek[1] <= REL_L2 and ev[0] <= MAX_ABS and ev[1] <= REL_L2
+    # whole tensor: the ring's O against the ordinary forward on the unsplit sequence
+    plan = fx.Plan(ctx, cu, Hq, Hkv, D, True)
+    o_full = torch.empty((S, Hq, D), dtype=torch.bfloat16, device="cuda")
+    l_full = torch.empty((Hq, S), dtype=torch.float32, device="cuda")
+    fx.flexsp_attn_varlen_fwd(ctx, plan, to_dev(q), kd, vd, None, o_full, l_full)
+    torch.cuda.synchronize()
+    plan.close()
+    d = (o_acc.float() - o_full[first:].float()).abs().max().item()
+    dl = (l_acc - l_full[:, first:]).abs().max().item()
+    say(f"  ring vs unsplit forward over all {C} rows: O max_abs={d:.2e} LSE max_abs={dl:.2e}")
+    assert d <= MAX_ABS and dl < 1e-3

@@ -530,7 +530,7 @@ def test_lse_merge_acc_keeps_the_running_result_in_fp32(ctx):
     e32 = errors(acc_d.cpu().numpy().astype(np.float64), Or)
     e16 = errors(bf16_f64(to_bits(run16)), Or)
     say(f"  sixteen parts folded: fp32 running result rel_l2={e32[1]:.2e}, bf16 running result rel_l2={e16[1]:.2e}")
-    assert e32[1] <= 1e-5 and e16[1] <= REL_L2 and e32[1] < e16[1] / 50
+    assert e32[1] <= 1e-5 and e16[1] <= 1e-2 and e32[1] < e16[1] / 50     # (fifteen bf16 roundings: about 5e-3)
     assert np.abs(lacc_d.cpu().numpy() - Lr).max() <= 1e-5
 
 

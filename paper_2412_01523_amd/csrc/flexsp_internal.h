@@ -31,6 +31,7 @@ constexpr int kLateTicketSteps = 16;  // items of at least this many steps draw 
 // kMaxSplitRecords records per pass.
 constexpr int kPartialBytes = 64 * kThreads * 4 + 2 * kThreads * 4;  // 67 584 B
 constexpr int kMinPartSteps = 16;
+constexpr int kGroupMajorSteps = 24;  // sequences whose longest tile has at most this many steps are queued tile beside tile
 constexpr int kLongPartSteps = 160;  // parts at least this long are aimed at 35 % of an even share instead of 75 %
 constexpr int kMaxParts = 8;
 constexpr int kMaxSplitRecords = 2048;

@@ -107,10 +107,27 @@ def test_plan_covers_every_tile_once_longest_first(host_ctx, causal):
     for which, heads in ((fx.PASS_FWD, hq), (fx.PASS_BWD_DKV, hkv), (fx.PASS_BWD_DQ, hq)):
         rows = plan.tile_rows(which)
         items, offs = _check_pass(plan, which, live if False else lens, heads, rows)
-        # inside a queue: cost (inner-loop steps of the item) never increases
+        # inside a queue: items of long sequences in order of decreasing cost (inner-loop steps); the tiles
+        # of a short sequence (none of more than 24 steps) side by side, dearest first, where the dearest
+        # of them would stand
+        cost = [_item_steps(i, which, causal, rows, hq // hkv) for i in items]
+        gmax = {}
+        for i, c in zip(items, cost):
+            key = (int(i["seq_start"]), int(i["head"]))
+            gmax[key] = max(gmax.get(key, 0), c)
         for x in range(len(offs) - 1):
-            steps = [_item_steps(i, which, causal, rows, hq // hkv) for i in items[offs[x]:offs[x + 1]]]
-            assert all(a >= b for a, b in zip(steps, steps[1:]))
+            seg = range(int(offs[x]), int(offs[x + 1]))
+            keys = [(int(items[n]["seq_start"]), int(items[n]["head"])) for n in seg]
+            rank = [cost[n] if gmax[k] > 24 else gmax[k] for n, k in zip(seg, keys)]
+            assert all(a >= b for a, b in zip(rank, rank[1:]))
+            seen, prev = set(), None
+            for n, k in zip(seg, keys):
+                if gmax[k] <= 24:
+                    assert k == prev or k not in seen          # a short sequence's tiles are contiguous ...
+                    if k == prev:
+                        assert cost[n] <= cost[n - 1]          # ... and ordered
+                    seen.add(k)
+                prev = k
         # tiles are cut when, and only when, they would outlast 3/4 of an even share of the pass over the
         # 512 workgroups a host-only context plans for; no part is shorter than 16 steps
         total = sum(_item_steps(i, which, causal, rows, hq // hkv) for i in items)

@@ -42,8 +42,8 @@ HBM_PEAK = 8.0e12           # MI355X HBM3E, B/s
 # counter values and the algorithmic bytes beside them are in profiles/attention_hbm_traffic.md).
 # bench.py cannot run the profiler on itself: these are the figures of that summary.
 MEASURED_HBM_TRAFFIC = {
-    ("pareto-64k", "fwd"): 1322061446, ("pareto-64k", "bwd_dq"): 1522143044, ("pareto-64k", "bwd_dkv"): 1613101153,
-    ("single-128k", "fwd"): 11688667937, ("single-128k", "bwd_dq"): 26337655680, ("single-128k", "bwd_dkv"): 10269544024,
+    ("pareto-64k", "fwd"): 1109401063, ("pareto-64k", "bwd_dq"): 1347854523, ("pareto-64k", "bwd_dkv"): 1284704310,
+    ("single-128k", "fwd"): 11779112005, ("single-128k", "bwd_dq"): 25981247295, ("single-128k", "bwd_dkv"): 10197784226,
 }
 
 

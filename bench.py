@@ -230,6 +230,51 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     return out
 
 
+def length_sweep_leg(ctx, fx, wl, torch, np):
+    """Attention fwd+bwd (8 heads, D = 128, causal) on batches of 49 152 tokens made of equal sequences of 256 ...
+    8 192 tokens, and on the short and the long sequences of the pareto-64k batch by themselves: what the
+    per-item costs of short sequences (paper Sec. 3: most sequences of a corpus are short) take from the
+    rate long sequences reach.  Per-kernel times from the library's event recorder, 20 steps after 5."""
+    H, D = 8, 128
+    pareto = wl.lengths(next(c for c in wl.CONFIGS if c.name == "pareto-64k"))
+    cases = [(f"{49152 // s} x {s}", [s] * (49152 // s)) for s in (256, 512, 1024, 2048, 4096, 8192)]
+    cases += [("pareto-64k, sequences <= 4000", [s for s in pareto if s <= 4000]),
+              ("pareto-64k, sequences > 4000", [s for s in pareto if s > 4000]), ("pareto-64k", pareto)]
+    out = []
+    for name, lens in cases:
+        cu = wl.cu_seqlens(lens)
+        T = int(cu[-1])
+        q = torch.randn((T, H, D), device="cuda").to(torch.bfloat16)
+        k, v, g = torch.randn_like(q), torch.randn_like(q), torch.randn_like(q)
+        o, dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        lse = torch.empty((H, T), dtype=torch.float32, device="cuda")
+        cud = torch.from_numpy(cu).cuda()
+        plan = fx.Plan(ctx, cu, H, H, D, True)
+
+        def step():
+            fx.flexsp_attn_varlen_fwd(ctx, plan, q, k, v, cud, o, lse)
+            fx.flexsp_attn_varlen_bwd(ctx, plan, q, k, v, o, g, lse, cud, dq, dk, dv)
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+        ctx.profile_start(128)
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+        pr = ctx.profile_stop()
+        plan.close()
+        ms = {n: pr[n][0] / max(pr[n][1], 1) for n in ("fwd", "bwd_dq", "bwd_dkv")}
+        f_fwd, f_bwd = wl.attn_flops(lens, H, D, True)
+        total = sum(ms.values())
+        io = 2 * T * H * D          # bytes of one bf16 [T, H, D] tensor
+        out.append({"batch": name, "tokens": T, "sequences": len(lens), "fwd_ms": ms["fwd"], "bwd_dq_ms": ms["bwd_dq"],
+                    "bwd_dkv_ms": ms["bwd_dkv"], "tflops": (f_fwd + f_bwd) / (total * 1e-3) / 1e12,
+                    "frac_of_bf16_mfma_peak": (f_fwd + f_bwd) / (total * 1e-3) / BF16_MFMA_PEAK,
+                    "fwd_flop_per_byte": f_fwd / (4 * io), "fwd_ms_of_its_bytes_at_6TBps": 4 * io / 6e12 * 1e3,
+                    "fwd_ms_of_its_flops_at_peak": f_fwd / BF16_MFMA_PEAK * 1e3})
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -251,6 +296,9 @@ def main() -> int:
                     help="for counter collection under rocprofv3 --pmc: 5 plain copies of known size (the permute "
                          "kernel with P = 1 on [32768, 32, 128] bf16: 256 MiB read, 256 MiB written each), then 3 x "
                          "(forward + backward) of the workload with one plan; nothing is timed")
+    ap.add_argument("--length-sweep", action="store_true",
+                    help="only the sequence-length leg: attention fwd+bwd on batches of equal sequences of 256 ... 8192 "
+                         "tokens and on the short and the long sequences of pareto-64k by themselves")
     ap.add_argument("--kvshard-ring", action="store_true",
                     help="only the context-parallel leg: one device's ring pass (forward against one key shard at a "
                          "time + merge, then the backward ring) on single-128k (8 shards) and pareto-64k (4 shards), beside the unsplit forward")
@@ -272,6 +320,12 @@ def main() -> int:
         torch.cuda.set_device(0)
         ctx = fx.Context(0)
         print(json.dumps({"cost_model": cost_model_leg(ctx, fx, wl, torch, np)}))
+        return 0
+
+    if args.length_sweep:
+        torch.cuda.set_device(0)
+        ctx = fx.Context(0)
+        print(json.dumps({"length_sweep": length_sweep_leg(ctx, fx, wl, torch, np)}))
         return 0
 
     if args.kvshard_ring:

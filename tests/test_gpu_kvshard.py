@@ -162,14 +162,18 @@ def _shard_backward(ctx, q, k, v, o_bits, g, lse, cu_q, cu_k, shift, causal, gra
     return host(dq), host(dk)[:Tk], host(dv)[:Tk]
 
 
-def _compare_grads(tag, got, ref, grad_f32, names=("dQ", "dK", "dV")):
+def _compare_grads(tag, got, ref, grad_f32, names=("dQ", "dK", "dV"), dq_is_a_part=False):
+    """dq_is_a_part: the shard holds only some of the keys the rows see.  Its share of dQ can then be a small
+    piece of the rows' gradient, while its error (delta from the rounded O, P rounded to bf16) is that of the
+    complete attention: the relative bound belongs to the sum over the shards, the part is held to max-abs."""
     for name, g_, r_ in zip(names, got, ref):
         assert np.isfinite(g_).all(), f"{tag} {name}: non-finite values"
         ma, rl = errors(g_, r_)
         say(f"  {tag} {name}: max_abs={ma:.2e} rel_l2={rl:.2e}")
         # (a gradient stored as bf16 carries its final rounding on top, up to 2^-8 of its value)
         tol = MAX_ABS if grad_f32 else MAX_ABS + np.abs(r_) * 2.0 ** -8
-        assert (np.abs(g_ - r_) <= tol).all() and rl <= REL_L2, f"{tag} {name}"
+        assert (np.abs(g_ - r_) <= tol).all(), f"{tag} {name}"
+        assert rl <= REL_L2 or (name == "dQ" and dq_is_a_part), f"{tag} {name}"
 
 
 @pytest.mark.parametrize("extra", [0, 37], ids=["shard-is-everything", "one-part-of-more"])
@@ -194,7 +198,7 @@ def test_kvshard_backward_matches_oracle_elementwise(ctx, name, lq, lk, shift, H
     o_bits = wl.f32_to_bf16_bits(O.astype(np.float32))
     for grad_f32 in (True, False):
         got = _shard_backward(ctx, q, k, v, o_bits, g, LSE, cu_q, cu_k, shift, causal, grad_f32)
-        _compare_grads(f"{name} {'fp32' if grad_f32 else 'bf16'}", got, ref, grad_f32)
+        _compare_grads(f"{name} {'fp32' if grad_f32 else 'bf16'}", got, ref, grad_f32, dq_is_a_part=extra > 0)
 
 
 @pytest.mark.parametrize("causal", [True, False])
@@ -289,7 +293,8 @@ def test_random_shard_configs_forward_and_backward(ctx, seed):
             top = float(np.abs(r_).max(initial=0.0))
             tol = max(MAX_ABS, REL_L2 * top) + (0.0 if grad_f32 else np.abs(r_) * 2.0 ** -8)
             say(f"  random {seed} {name} {'fp32' if grad_f32 else 'bf16'}: max_abs={ma:.2e} rel_l2={rl:.2e} (largest value {top:.1f})")
-            assert (np.abs(g_ - r_) <= tol).all() and rl <= REL_L2, name
+            assert (np.abs(g_ - r_) <= tol).all(), name
+            assert rl <= REL_L2 or (name == "dQ" and extra > 0), name      # (a part of dQ: see _compare_grads)
 
 
 def test_four_emulated_devices_ring_forward_and_backward_equal_the_unsplit_attention(ctx):

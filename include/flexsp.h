@@ -90,7 +90,8 @@ int flexsp_ctx_num_xcd(const flexsp_ctx *ctx);
  *   causal           nonzero: key j of a sequence is visible to query i iff j <= i.
  * The plan lists work items (sequence, tile, head; the longest tiles cut into parts when few
  * heads and a dominant sequence would leave compute units waiting for them, see flexsp_item),
- * longest first, in one queue per XCD, for the forward kernel and for the two backward kernels,
+ * longest first (the tiles of a short sequence side by side, where its longest tile would stand),
+ * in one queue per XCD, for the forward kernel and for the two backward kernels,
  * and holds the fp32 scratch the kernels need (delta and the base-2 log-sum-exp [Hq, T] for the
  * backward, one 66 KiB record per part of a cut tile), so the hot calls allocate nothing.
  * Everything is copied before the call returns; the caller keeps ownership of

@@ -20,6 +20,10 @@ per second over the whole step, inputs resident in HBM.  `roofline` describes th
 kernel, timed with HIP events recorded by the library around each of its launches on the
 stream they run on.  `cpu_baseline` times the CPU fp64 oracle on a bounded sample of the same
 workload (a reported baseline, not a target).
+
+Other legs, each printing one JSON line of its own and nothing else: --cost-model (the paper's Eq. 12 fitted to
+these kernels), --kvshard-ring (one device's pass of a context-parallel ring, forward and backward),
+--length-sweep (attention by sequence length), --permute-only and --traffic-probe (for counter collection).
 """
 from __future__ import annotations
 

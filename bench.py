@@ -107,7 +107,7 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     parallelism, and the appendix that integrates it): the device holds the LAST 1/P of every sequence's
     query rows (the rank with the most visible keys, which sets the ring's time), the key/value shards come
     by one at a time (its own first, then the earlier ones), each gives a partial attention
-    (flexsp_attn_varlen_fwd_kvshard) that is folded into the fp32 running result (flexsp_lse_merge_acc);
+    that the shard forward itself folds into the fp32 running result (flexsp_attn_varlen_fwd_kvshard_acc);
     then the backward ring (flexsp_attn_varlen_bwd_kvshard with accumulate, fp32 partial sums).
     Plans are built beforehand (lengths are known on the host); timed with events on the stream."""
     cfg = next(c for c in wl.CONFIGS if c.name == workload)
@@ -139,7 +139,6 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     o_acc = torch.empty((Tq, H, D), dtype=torch.bfloat16, device=dev)      # the complete O, rounded to bf16 once
     o_run = torch.empty((Tq, H, D), dtype=torch.float32, device=dev)       # the running result, fp32
     l_acc = torch.empty((H, Tq), dtype=torch.float32, device=dev)
-    o_new, l_new = torch.empty_like(o_acc), torch.empty_like(l_acc)
     stream = torch.cuda.current_stream()
     reps = 10
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * P)] for _ in range(reps)]
@@ -147,9 +146,9 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     def one_pass(marks):
         l_acc.fill_(float("-inf"))       # an empty running result (its O may hold anything)
         for n, sh in enumerate(shards):
-            fx.flexsp_attn_varlen_fwd_kvshard(ctx, sh["plan"], q, sh["k"], sh["v"], o_new, l_new, stream=stream)
+            fx.flexsp_attn_varlen_fwd_kvshard_acc(ctx, sh["plan"], q, sh["k"], sh["v"], o_run, l_acc,
+                                                  o_acc if n == P - 1 else None, stream=stream)
             if marks: marks[2 * n].record(stream)
-            fx.flexsp_lse_merge_acc(ctx, o_run, l_acc, o_new, l_new, o_acc if n == P - 1 else None, stream)
             if marks: marks[2 * n + 1].record(stream)
 
     for _ in range(3):
@@ -195,7 +194,6 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     bwd_ms = np.array([[bev[r][n].elapsed_time(bev[r][n + 1]) for n in range(P)] for r in range(reps)])
     bwd_med = np.median(bwd_ms, axis=0)
     bwd_total = float(np.median([bev[r][0].elapsed_time(bev[r][P]) for r in range(reps)]))
-    merge_bytes = Tq * H * D * (4 + 2 + 4) + 3 * H * Tq * 4     # fp32 running result read and written, one bf16 part read
     # the ordinary forward over the unsplit batch, for the rate the shard kernel is measured against
     plan = fx.Plan(ctx, cu, H, Hkv, D, True)
     o_full = torch.empty_like(q_full)
@@ -221,7 +219,7 @@ def ring_leg(ctx, fx, wl, torch, np, workload):
     out = {"workload": cfg.name, "ring_degree": P, "query_rows": Tq, "heads": H, "head_dim": D,
            "shards": [{"shard": sh["shard"], "ms": float(fwd_med[n]), "tflops": sh["flops"] / (fwd_med[n] * 1e-3) / 1e12}
                       for n, sh in enumerate(shards)],
-           "merge_ms_each": float(np.median(mrg_med[:-1])), "merge_GBps": merge_bytes / (np.median(mrg_med[:-1]) * 1e-3) / 1e9,
+           "fold": "inside the shard forward (flexsp_attn_varlen_fwd_kvshard_acc): no merge launches",
            "pass_ms": total_ms, "pass_tflops": flops / (total_ms * 1e-3) / 1e12,
            "shard_forwards_tflops": flops / (fwd_med.sum() * 1e-3) / 1e12,
            "unsplit_forward_ms": full_ms, "unsplit_forward_tflops": full_flops / (full_ms * 1e-3) / 1e12,

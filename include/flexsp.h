@@ -254,7 +254,7 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
  *   |shift| <= 2^30) = position of sequence b's first query inside the full sequence minus position of
  *   the shard's first key: with `causal`, shard key j is visible to query row i iff j <= i + shift[b];
  *   without, every shard key is visible and shift is ignored.  The plan serves
- *   flexsp_attn_varlen_fwd_kvshard and flexsp_attn_varlen_bwd_kvshard only (the other attention calls
+ *   flexsp_attn_varlen_fwd_kvshard (_acc) and flexsp_attn_varlen_bwd_kvshard only (the other attention calls
  *   answer PLAN_MISMATCH); it is destroyed by flexsp_plan_destroy and inspected by flexsp_plan_num_items /
  *   _get_items, where an item's seq_start holds the sequence INDEX b (and, in FLEXSP_PASS_BWD_DKV, tile
  *   counts 64-key tiles of the SHARD).  Long query tiles are cut into parts as in flexsp_plan_create (a
@@ -263,6 +263,14 @@ int flexsp_attn_varlen_bwd(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, 
  * flexsp_attn_varlen_fwd_kvshard - per query row, softmax over the visible shard keys only:
  *   O = sum_j P_j v_j (bf16), LSE = log sum_j exp(scale q.k_j) (fp32, natural log, [head_count, Tq]).
  *   A row that sees no key of the shard gets O = 0 and LSE = -inf.  Arguments as flexsp_attn_varlen_fwd.
+ *
+ * flexsp_attn_varlen_fwd_kvshard_acc - the same attention folded straight into the fp32 running result of a
+ *   ring, without writing the shard's own O and LSE and without a merge pass:
+ *   (o_acc, lse_acc) <- merge((o_acc, lse_acc), (O, LSE) of the rows over this shard), as flexsp_lse_merge_acc
+ *   does it (below), except that the shard's O enters in fp32, unrounded.  o_acc: view of [Tq, Hq, D] FP32;
+ *   lse_acc fp32 [head_count, Tq]; start a ring with lse_acc = -inf (o_acc may then hold anything).  If
+ *   o_bf16.ptr is not NULL the merged rows are also written there rounded to bf16 (view of [Tq, Hq, D]).
+ *   Calls on the same o_acc must be ordered (one stream).
  *
  * flexsp_attn_varlen_bwd_kvshard - the backward's share of one key shard (gradient of Eq. 3 restricted to
  *   the shard's keys), for the same plan.  `lse` ([head_count, Tq] fp32, natural log) must be each row's
@@ -303,6 +311,10 @@ int flexsp_attn_varlen_fwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_te
                                    flexsp_tensor v, int32_t head_begin, int32_t head_count, int32_t kv_head_begin,
                                    int32_t kv_head_count, int causal, float softmax_scale, flexsp_tensor o,
                                    float *lse, flexsp_stream stream);
+int flexsp_attn_varlen_fwd_kvshard_acc(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                                       flexsp_tensor v, int32_t head_begin, int32_t head_count,
+                                       int32_t kv_head_begin, int32_t kv_head_count, int causal, float softmax_scale,
+                                       flexsp_tensor o_acc, float *lse_acc, flexsp_tensor o_bf16, flexsp_stream stream);
 int flexsp_attn_varlen_bwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
                                    flexsp_tensor v, flexsp_tensor o, flexsp_tensor dO, const float *lse,
                                    int32_t head_begin, int32_t head_count, int32_t kv_head_begin,

@@ -26,7 +26,7 @@ EXPORTS = (
     "flexsp_plan_tile_rows", "flexsp_attn_bwd_workspace_bytes",
     "flexsp_pack", "flexsp_unpack", "flexsp_pack_many", "flexsp_unpack_many",
     "flexsp_attn_varlen_fwd", "flexsp_attn_varlen_bwd", "flexsp_attn_varlen_fwd_static",
-    "flexsp_plan_create_kvshard", "flexsp_attn_varlen_fwd_kvshard", "flexsp_attn_varlen_bwd_kvshard", "flexsp_lse_merge", "flexsp_lse_merge_acc",
+    "flexsp_plan_create_kvshard", "flexsp_attn_varlen_fwd_kvshard", "flexsp_attn_varlen_fwd_kvshard_acc", "flexsp_attn_varlen_bwd_kvshard", "flexsp_lse_merge", "flexsp_lse_merge_acc",
     "flexsp_profile_start", "flexsp_profile_stop",
     "flexsp_bucket_dp", "flexsp_chunk_dp", "flexsp_min_microbatches",
 )
@@ -109,6 +109,9 @@ def lib() -> ctypes.CDLL:
                                                  c_int32, c_int, POINTER(c_void_p)]
         L.flexsp_attn_varlen_fwd_kvshard.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, c_int32, c_int32,
                                                      c_int32, c_int32, c_int, c_float, Tensor, c_void_p, c_void_p]
+        L.flexsp_attn_varlen_fwd_kvshard_acc.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, c_int32, c_int32,
+                                                         c_int32, c_int32, c_int, c_float, Tensor, c_void_p, Tensor,
+                                                         c_void_p]
         L.flexsp_attn_varlen_bwd_kvshard.argtypes = [c_void_p, c_void_p, Tensor, Tensor, Tensor, Tensor, Tensor, c_void_p,
                                                      c_int32, c_int32, c_int32, c_int32, c_int, c_float, Tensor, Tensor,
                                                      Tensor, c_int32, c_int32, c_void_p]
@@ -332,6 +335,22 @@ def flexsp_attn_varlen_fwd_kvshard(ctx: Context, plan: ShardPlan, q, k, v, o, ls
                                                 head_count, kv_head_begin, kv_head_count, int(bool(causal)),
                                                 float(softmax_scale), _view(o), lse.data_ptr(), _stream(stream)),
            "flexsp_attn_varlen_fwd_kvshard")
+
+
+def flexsp_attn_varlen_fwd_kvshard_acc(ctx: Context, plan: ShardPlan, q, k, v, o_acc, lse_acc, o_bf16=None, *, head_begin=0,
+                                       head_count=None, kv_head_begin=0, kv_head_count=None, causal=True,
+                                       softmax_scale=0.0, stream=None):
+    """o_acc [Tq,Hq,D] fp32 view and lse_acc [Hq,Tq] fp32: the ring's running result, updated in place; o_bf16:
+    optional bf16 [Tq,Hq,D] view that receives the merged rows rounded once."""
+    import torch
+    assert o_acc.dtype == torch.float32 and lse_acc.is_contiguous()
+    head_count = plan.hq if head_count is None else head_count
+    kv_head_count = plan.hkv if kv_head_count is None else kv_head_count
+    _check(lib().flexsp_attn_varlen_fwd_kvshard_acc(ctx.handle, plan.handle, _view(q), _view(k), _view(v), head_begin,
+                                                    head_count, kv_head_begin, kv_head_count, int(bool(causal)),
+                                                    float(softmax_scale), _view(o_acc), lse_acc.data_ptr(),
+                                                    Tensor(None, 0, 0) if o_bf16 is None else _view(o_bf16),
+                                                    _stream(stream)), "flexsp_attn_varlen_fwd_kvshard_acc")
 
 
 def flexsp_attn_varlen_bwd_kvshard(ctx: Context, plan: ShardPlan, q, k, v, o, dO, lse, dq, dk, dv, *, head_begin=0,

@@ -101,6 +101,24 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
             if (kv_end <= 0) {
                 // no row of this item sees a key of the shard: O = 0, LSE = -inf (the neutral element
                 // of the merge); deal.advance() holds the barrier every item ends with
+                if (a.dq) {
+                    // folding into a running result: it stays as it is; only its bf16 copy, if asked for, is written
+                    if (a.out_o) {
+                        for (int idx = tid; idx < kFwdBq * L::CH; idx += kThreads) {
+                            const int row = q0 + idx / L::CH;
+                            if (row >= s) continue;
+                            const bool live = a.delta_out[(int64_t)h * a.T + tok0 + row] > -INFINITY;
+                            const float *src = (const float *)a.dq + (tok0 + row) * a.dq_st + (int64_t)h * a.dq_sh + (idx % L::CH) * 8;
+                            const f32x4 x0 = *(const f32x4 *)src, x1 = *(const f32x4 *)(src + 4);
+                            u32x4 y = {pack_bf16x2(x0[0], x0[1]), pack_bf16x2(x0[2], x0[3]), pack_bf16x2(x1[0], x1[1]),
+                                       pack_bf16x2(x1[2], x1[3])};
+                            if (!live) y = u32x4{0, 0, 0, 0};
+                            *(u32x4 *)(a.out_o + (tok0 + row) * a.o_st + (int64_t)h * a.o_sh + (idx % L::CH) * 8) = y;
+                        }
+                    }
+                    deal.prefetch();
+                    continue;
+                }
                 for (int idx = tid; idx < kFwdBq * L::CH; idx += kThreads) {
                     const int row = q0 + idx / L::CH;
                     if (row < s)
@@ -483,6 +501,47 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const AttnArgs a)
                     }
                 }
                 m_run = M;
+            }
+        }
+        if constexpr (SHARD) {
+            if (a.dq) {
+                // Fold into the fp32 running result of a ring instead of writing this shard's own O and LSE:
+                // (o_acc, lse_acc) <- merge((o_acc, lse_acc), (O, LSE)), the row's two half-wave lanes each
+                // taking their head-dim elements of the row; a part that counts nothing is silenced even
+                // if it holds rubbish (a running result is started with lse_acc = -inf over anything).
+                if (qrow < s) {
+                    const int64_t li = (int64_t)h * a.T + tok0 + qrow;
+                    const float la = a.delta_out[li];
+                    const float lb = l_tot > 0.f ? m_run * a.scale + __logf(l_tot) : -INFINITY;
+                    const float m = fmaxf(la, lb);
+                    float wa = 0.f, wb = 0.f, lse = -INFINITY;
+                    if (m > -INFINITY) {
+                        const float ea = __expf(la - m), eb = __expf(lb - m);
+                        const float inv = 1.0f / (ea + eb);
+                        wa = ea * inv;
+                        wb = l_tot > 0.f ? eb * inv / l_tot : 0.f;  // (with the row's normalisation)
+                        lse = m + __logf(ea + eb);
+                    }
+                    float *row = (float *)a.dq + (tok0 + qrow) * a.dq_st + (int64_t)h * a.dq_sh;
+#pragma unroll
+                    for (int db = 0; db < DB; db++)
+#pragma unroll
+                        for (int i4 = 0; i4 < 4; i4++) {
+                            f32x4 *p = (f32x4 *)(row + db * 32 + 8 * i4 + 4 * hl);
+                            f32x4 w = *p;
+#pragma unroll
+                            for (int e = 0; e < 4; e++) {
+                                w[e] = (wa > 0.f ? wa * w[e] : 0.f) + wb * oacc[db][4 * i4 + e];
+                                oacc[db][4 * i4 + e] = w[e];
+                            }
+                            *p = w;
+                        }
+                    if (hl == 0) a.delta_out[li] = lse;  // (after both lanes of the row have read it: one wavefront)
+                }
+                if (a.out_o && wq_lo < s)  // the merged rows rounded to bf16, if asked for
+                    store_rowT_bf16_lds<DB>(smem + wave * (32 * L::ROWB), a.out_o + (tok0 + wq_lo) * a.o_st + (int64_t)h * a.o_sh,
+                                            a.o_st, min(32, s - wq_lo), oacc, 1.0f, lane);
+                continue;
             }
         }
         if (qrow < s && hl == 0) a.lse_out[(int64_t)h * a.T + tok0 + qrow] = m_run * a.scale + __logf(l_tot);

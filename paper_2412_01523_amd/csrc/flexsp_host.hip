@@ -1047,6 +1047,55 @@ int flexsp_attn_varlen_fwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_te
     return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
 }
 
+int flexsp_attn_varlen_fwd_kvshard_acc(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
+                                       flexsp_tensor v, int32_t head_begin, int32_t head_count, int32_t kv_head_begin,
+                                       int32_t kv_head_count, int causal, float scale, flexsp_tensor o_acc,
+                                       float *lse_acc, flexsp_tensor o_bf16, flexsp_stream stream)
+{
+    if (!ctx || !plan) return FLEXSP_INVALID_ARGUMENT;
+    if (plan->ctx != ctx || !plan->kvshard) return FLEXSP_PLAN_MISMATCH;
+    if (head_begin < 0 || kv_head_begin < 0 || head_count <= 0 || kv_head_count <= 0 ||
+        head_count % kv_head_count != 0)
+        return FLEXSP_INVALID_ARGUMENT;
+    if (head_count != plan->Hq || kv_head_count != plan->Hkv || (causal != 0) != (plan->causal != 0))
+        return FLEXSP_PLAN_MISMATCH;
+    if (!view_ok(q) || !view_ok(k) || !view_ok(v) || !view_ok(o_acc) || (o_bf16.ptr && !view_ok(o_bf16)) || !lse_acc ||
+        !std::isfinite(scale))
+        return FLEXSP_INVALID_ARGUMENT;
+    if (ctx->device < 0 || !plan->dev_base) return FLEXSP_NO_DEVICE;
+    if (plan->pass[FLEXSP_PASS_FWD].items.empty()) return FLEXSP_OK;
+    {
+        hipError_t pe = plan_before_launch(plan, (hipStream_t)stream);
+        if (pe != hipSuccess) return hip_fail(pe);
+    }
+    if (scale <= 0.f) scale = 1.0f / std::sqrt((float)plan->D);
+    AttnArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.q = (const uint16_t *)q.ptr + (int64_t)head_begin * q.stride_head;
+    a.k = (const uint16_t *)k.ptr + (int64_t)kv_head_begin * k.stride_head;
+    a.v = (const uint16_t *)v.ptr + (int64_t)kv_head_begin * v.stride_head;
+    // the kernel's fold mode: the fp32 running result travels in the fields the forward does not use otherwise
+    a.dq = (float *)o_acc.ptr + (int64_t)head_begin * o_acc.stride_head;
+    a.dq_st = (int32_t)o_acc.stride_token; a.dq_sh = (int32_t)o_acc.stride_head;
+    a.delta_out = lse_acc;
+    if (o_bf16.ptr) {
+        a.out_o = (uint16_t *)o_bf16.ptr + (int64_t)head_begin * o_bf16.stride_head;
+        a.o_st = (int32_t)o_bf16.stride_token; a.o_sh = (int32_t)o_bf16.stride_head;
+    }
+    a.q_st = (int32_t)q.stride_token; a.q_sh = (int32_t)q.stride_head;
+    a.k_st = (int32_t)k.stride_token; a.k_sh = (int32_t)k.stride_head;
+    a.v_st = (int32_t)v.stride_token; a.v_sh = (int32_t)v.stride_head;
+    a.T = (int32_t)plan->T; a.Hq = plan->Hq; a.G = plan->Hq / plan->Hkv; a.causal = plan->causal;
+    a.scale = scale; a.scale_l2 = scale * 1.4426950408889634f;
+    a.pq = plan->dq[FLEXSP_PASS_FWD];
+    hipError_t e;
+    {
+        Timed tm(ctx, FLEXSP_K_FWD, (hipStream_t)stream);
+        e = launch_attn_fwd_kvshard(a, plan->D, grid_for(ctx, plan->pass[FLEXSP_PASS_FWD], 2), (hipStream_t)stream);
+    }
+    return e == hipSuccess ? FLEXSP_OK : hip_fail(e);
+}
+
 int flexsp_attn_varlen_bwd_kvshard(flexsp_ctx *ctx, flexsp_plan *plan, flexsp_tensor q, flexsp_tensor k,
                                    flexsp_tensor v, flexsp_tensor o, flexsp_tensor dO, const float *lse,
                                    int32_t head_begin, int32_t head_count, int32_t kv_head_begin,

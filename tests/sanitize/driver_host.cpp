@@ -92,10 +92,14 @@ int main()
             CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, sp, t, t, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_F32, 2, nullptr) == FLEXSP_INVALID_ARGUMENT);
             CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, sp, t, bad, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_F32, 1, nullptr) == FLEXSP_INVALID_ARGUMENT);
             CHECK(flexsp_attn_varlen_bwd_kvshard(ctx, sp, t, t, t, t, t, lse, 0, 2, 0, 2, 1, 0.f, t, t, t, FLEXSP_F32, 1, nullptr) == FLEXSP_NO_DEVICE);
+            CHECK(flexsp_attn_varlen_fwd_kvshard_acc(ctx, sp, t, t, t, 0, 2, 0, 2, 1, 0.f, t, lse, flexsp_tensor{nullptr, 0, 0}, nullptr) == FLEXSP_NO_DEVICE);
+            CHECK(flexsp_attn_varlen_fwd_kvshard_acc(ctx, sp, t, t, t, 0, 2, 0, 2, 1, 0.f, t, nullptr, t, nullptr) == FLEXSP_INVALID_ARGUMENT);
+            CHECK(flexsp_attn_varlen_fwd_kvshard_acc(ctx, sp, t, t, t, 0, 2, 0, 2, 1, 0.f, t, lse, bad, nullptr) == FLEXSP_INVALID_ARGUMENT);
             flexsp_plan_destroy(sp);
         }
         CHECK(flexsp_lse_merge(ctx, t, lse, t, lse, t, lse, 8, 2, 64, nullptr) == FLEXSP_NO_DEVICE);
         CHECK(flexsp_lse_merge(ctx, t, lse, t, lse, t, lse, 8, 2, 40, nullptr) == FLEXSP_UNSUPPORTED);
+        CHECK(flexsp_attn_varlen_fwd_kvshard_acc(ctx, p, t, t, t, 0, 2, 0, 2, 1, 0.f, t, lse, flexsp_tensor{nullptr, 0, 0}, nullptr) == FLEXSP_PLAN_MISMATCH);
         CHECK(flexsp_lse_merge_acc(ctx, t, lse, t, lse, flexsp_tensor{nullptr, 0, 0}, 8, 2, 64, nullptr) == FLEXSP_NO_DEVICE);
         CHECK(flexsp_lse_merge_acc(ctx, t, lse, t, lse, bad, 8, 2, 64, nullptr) == FLEXSP_INVALID_ARGUMENT);
         CHECK(flexsp_lse_merge_acc(ctx, t, nullptr, t, lse, t, 8, 2, 64, nullptr) == FLEXSP_INVALID_ARGUMENT);

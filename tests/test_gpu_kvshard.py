@@ -344,8 +344,11 @@ def test_four_emulated_devices_ring_forward_and_backward_equal_the_unsplit_atten
         o_new = torch.empty_like(o_acc)
         l_new = torch.empty((Hq, Tq), dtype=torch.float32, device="cuda")
         for j in [(r - i) % P for i in range(P)]:                    # its own shard first, then round the ring
-            fx.flexsp_attn_varlen_fwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o_new, l_new)
-            fx.flexsp_lse_merge_acc(ctx, o_run, l_acc, o_new, l_new, o_acc)
+            if j % 2:                                                 # (both ways of folding, alternately)
+                fx.flexsp_attn_varlen_fwd_kvshard_acc(ctx, plans[j], qd, kd[j], vd[j], o_run, l_acc, o_acc)
+            else:
+                fx.flexsp_attn_varlen_fwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o_new, l_new)
+                fx.flexsp_lse_merge_acc(ctx, o_run, l_acc, o_new, l_new, o_acc)
         dq = torch.zeros((Tq, Hq, D), dtype=torch.float32, device="cuda")
         for j in [(r - i) % P for i in range(P)]:
             fx.flexsp_attn_varlen_bwd_kvshard(ctx, plans[j], qd, kd[j], vd[j], o_acc, gd, l_acc, dq, dk[j], dv[j],
@@ -539,6 +542,55 @@ def test_lse_merge_acc_keeps_the_running_result_in_fp32(ctx):
     assert np.abs(lacc_d.cpu().numpy() - Lr).max() <= 1e-5
 
 
+@pytest.mark.parametrize("name,lq,lk,shift,Hq,Hkv,D,causal", SHARD_CASES + CUT_CASES, ids=[c[0] for c in SHARD_CASES + CUT_CASES])
+def test_kvshard_forward_folded_into_a_running_result(ctx, name, lq, lk, shift, Hq, Hkv, D, causal):
+    """flexsp_attn_varlen_fwd_kvshard_acc = the shard's attention merged into (o_acc, lse_acc), against the
+    oracle's shard attention merged by the oracle's merge: from an empty running result (lse = -inf over NaN)
+    and from one that holds numbers; the fp32 rows to fp32-with-bf16-operands accuracy (the stated O bounds),
+    the bf16 copy = the fp32 rows rounded once, rows that have seen no key anywhere: LSE = -inf, bf16 copy 0."""
+    import torch
+    from paper_2412_01523_amd import binding as fx
+    say(f"folded key-shard case {name}: queries {lq} keys {lk} shift {shift} Hq={Hq} Hkv={Hkv} D={D} causal={causal}")
+    seed = 6300 + len(name)
+    Tq = sum(lq)
+    q = wl.normal_bf16(seed, wl.TID_Q, (Tq, Hq, D))
+    k = wl.normal_bf16(seed, wl.TID_K, (sum(lk), Hkv, D))
+    v = wl.normal_bf16(seed, wl.TID_V, (sum(lk), Hkv, D))
+    cu_q, cu_k = wl.cu_seqlens(lq), wl.cu_seqlens(lk)
+    O1, L1 = oracle.attn_fwd_kvshard(q, k, v, cu_q, cu_k, shift, causal)
+    rng = np.random.default_rng(seed)
+    prev_o = rng.standard_normal((Tq, Hq, D)).astype(np.float32)
+    prev_l = rng.normal(2.0, 2.0, (Hq, Tq)).astype(np.float32)
+    prev_l[:, ::9] = -np.inf
+    plan = fx.ShardPlan(ctx, cu_q, cu_k, shift, Hq, Hkv, D, causal)
+    kd = to_dev(k) if len(k) else torch.zeros((8, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    vd = to_dev(v) if len(v) else torch.zeros((8, Hkv, D), dtype=torch.bfloat16, device="cuda")
+    for tag, start_o, start_l in (("from nothing", np.full((Tq, Hq, D), np.nan, dtype=np.float32), np.full((Hq, Tq), -np.inf, dtype=np.float32)),
+                                  ("onto a result", prev_o, prev_l)):
+        want_o, want_l = oracle.lse_merge(np.nan_to_num(start_o.astype(np.float64)), start_l, O1, L1)
+        o_acc, l_acc = torch.from_numpy(start_o.copy()).cuda(), torch.from_numpy(start_l.copy()).cuda()
+        if tag == "onto a result":
+            o_acc[::9] = float("nan")                 # rows whose running result is empty may hold anything
+        o16 = torch.full((Tq, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        fx.flexsp_attn_varlen_fwd_kvshard_acc(ctx, plan, to_dev(q), kd, vd, o_acc, l_acc, o16, causal=causal)
+        torch.cuda.synchronize()
+        got_l = l_acc.cpu().numpy().astype(np.float64)
+        dead = np.isneginf(want_l)
+        assert (np.isneginf(got_l) == dead).all(), f"{name} {tag}: rows without any key differ"
+        live = ~dead.T
+        got = o_acc.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got[live]).all()
+        ma, rl = errors(got[live], want_o[live])
+        el = float(np.abs(got_l[~dead] - want_l[~dead]).max(initial=0.0))
+        say(f"  {name} {tag}: O max_abs={ma:.2e} rel_l2={rl:.2e} LSE max_abs={el:.2e} rows without any key={int(dead.sum())}")
+        assert ma <= MAX_ABS and rl <= REL_L2 and el < 1e-3
+        got16 = bf16_f64(to_bits(o16))
+        assert not got16[dead.T].any()
+        # (rows that stay empty keep whatever o_acc held: only the live rows of the copy are the rounded fp32 rows)
+        assert np.array_equal(to_bits(o16)[live], to_bits(o_acc.to(torch.bfloat16))[live])
+    plan.close()
+
+
 def test_kvshard_error_paths(ctx):
     import torch
     from paper_2412_01523_amd import binding as fx
@@ -561,8 +613,8 @@ def test_kvshard_error_paths(ctx):
 
 def test_ring_at_bench_size_sampled_against_the_oracle(ctx):
     """The configuration `bench.py --kvshard-ring` times: the 131 072-token sequence (8 heads, D = 128) over a
-    ring of 8, the device with the last 16 384 query rows, forward ring (8 shard forwards folded into an fp32
-    running result) and
+    ring of 8, the device with the last 16 384 query rows, forward ring (8 shard forwards, each folding its
+    result into the fp32 running one) and
     backward ring (8 shard backwards, fp32 accumulation).  The oracle cannot run that in full inside a test;
     compared are outputs it computes one by one on the unsplit sequence: sampled rows of O, LSE and dQ (complete
     after the last shard), and late rows of dK / dV of the device's OWN shard, whose keys no other device's
@@ -587,8 +639,8 @@ def test_ring_at_bench_size_sampled_against_the_oracle(ctx):
     l_new = torch.empty((Hq, C), dtype=torch.float32, device="cuda")
     order = list(range(P - 1, -1, -1))
     for j in order:
-        fx.flexsp_attn_varlen_fwd_kvshard(ctx, plans[j], qd, kd[j * C:(j + 1) * C], vd[j * C:(j + 1) * C], o_new, l_new)
-        fx.flexsp_lse_merge_acc(ctx, o_run, l_acc, o_new, l_new, o_acc)
+        fx.flexsp_attn_varlen_fwd_kvshard_acc(ctx, plans[j], qd, kd[j * C:(j + 1) * C], vd[j * C:(j + 1) * C], o_run, l_acc,
+                                              o_acc if j == order[-1] else None)
     dq = torch.zeros((C, Hq, D), dtype=torch.float32, device="cuda")
     dk_own = torch.zeros((C, Hkv, D), dtype=torch.float32, device="cuda")
     dv_own = torch.zeros((C, Hkv, D), dtype=torch.float32, device="cuda")
